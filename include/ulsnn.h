@@ -1,0 +1,158 @@
+/*
+ * ulsnn -- single-precision GEMM and the one-hidden-layer MLP gradient built on it, for AMD MI355X (gfx950).
+ *
+ * The two operations are the hot path of the training method of "92c/MFlops/s, Ultra-Large-Scale
+ * Neural-Network Training on a PIII Cluster": a Level-3 BLAS SGEMM (section 3) and the error gradient of a
+ * one-hidden-layer network computed as a series of matrix products (section 4.2), summed over the training
+ * patterns (section 4.3).
+ *
+ * Conventions shared by every entry point
+ *   - All matrix and vector pointers are DEVICE pointers owned by the caller.  The library borrows them until
+ *     the work it queued on the stream has run.  Nothing is copied to or from the host.
+ *   - Matrices are ROW-major.  A leading dimension (lda, ldb, ldc) is the distance, in elements, between the
+ *     starts of consecutive rows (the "stride" of section 3.4); it may exceed the row length.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only queue work:
+ *     they return before it has run, and work of one call is ordered on that stream.
+ *   - Every function returns a ulsnn_status.  Arguments are checked on the host BEFORE any HIP call; a call
+ *     that returns ULSNN_ERR_NULL..ULSNN_ERR_UNSUPPORTED has queued nothing and touched no memory.
+ *     ULSNN_ERR_HIP reports a failed launch (hipGetLastError after the launch).
+ *   - No entry point allocates or frees device memory.  Scratch space comes from the caller (workspace).
+ *   - Input operands must not overlap outputs.
+ */
+#ifndef ULSNN_H
+#define ULSNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ulsnn_status {
+    ULSNN_OK = 0,
+    ULSNN_ERR_NULL = 1,        /* a required pointer is NULL                                   */
+    ULSNN_ERR_TRANS = 2,       /* transa / transb is not one of N n T t C c                    */
+    ULSNN_ERR_DIM = 3,         /* a negative size, or a network dimension < 1                  */
+    ULSNN_ERR_LD = 4,          /* a leading dimension smaller than the stored row length       */
+    ULSNN_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned (256 B) or smaller than required  */
+    ULSNN_ERR_UNSUPPORTED = 6, /* a documented option this build does not implement            */
+    ULSNN_ERR_HIP = 7          /* the HIP runtime refused a launch                             */
+} ulsnn_status;
+
+/*
+ * SGEMM:  C = alpha * op(A) * op(B) + beta * C        (section 3.1; Level-3 BLAS SGEMM interface, row-major)
+ *
+ *   op(X) = X for trans 'N'/'n', X^T for 'T'/'t' ('C'/'c' is accepted and means 'T').
+ *   op(A) is m x k, op(B) is k x n, C is m x n.  As stored, A is m x k ('N') or k x m ('T'), B is k x n ('N')
+ *   or n x k ('T').  lda >= max(1, stored row length of A), likewise ldb; ldc >= max(1, n).
+ *   Counts 2*m*n*k floating-point operations.
+ *
+ *   Reference-BLAS rules: m == 0 or n == 0 returns ULSNN_OK and touches nothing; k == 0 or alpha == 0 gives
+ *   C = beta*C; with beta == 0, C is written WITHOUT being read (NaN or Inf already in C do not propagate).
+ *   Only the m x n entries of C are written; padding columns (n .. ldc-1) are left as they are.
+ *   Products are accumulated in fp32 on the matrix cores; the order of summation is unspecified.
+ *   A, B read-only; pointers need only 4-byte alignment.  A or B NULL is an error unless that operand is
+ *   never read (m, n == 0, or k == 0, or alpha == 0).
+ */
+int ulsnn_sgemm(char transa, char transb, int m, int n, int k, float alpha, const float *A, int lda,
+                const float *B, int ldb, float beta, float *C, int ldc, void *hip_stream);
+
+/*
+ * Description of the network and of one gradient call (everything the 8-argument call below cannot carry).
+ *
+ *   Network (section 4.1, with the weight matrices stored transposed with respect to the paper's W_ih, W_ho):
+ *     W1 is n_in x n_hid, W2 is n_hid x n_out, both dense row-major.
+ *   b1[n_hid], b2[n_out]: optional biases.  The paper's network has none (section 5.1 counts
+ *     400*480 + 480*3203 parameters): pass NULL for both.  If given, db1/db2 receive their gradients
+ *     (b1, b2, db1, db2 are all NULL or all non-NULL).
+ *   accumulate: 0 -> dW1, dW2, db1, db2 and loss are overwritten;
+ *               1 -> the call ADDS to them (gradient and error are additive over patterns, section 4.3;
+ *                    this is how an epoch is summed over chunks of patterns).
+ *   operand_dtype: 0 = fp32 storage.  1 = bf16 storage of X, W1, W2 with fp32 accumulation: reserved,
+ *                    returns ULSNN_ERR_UNSUPPORTED in this build.
+ *   workspace: device scratch of at least ulsnn_mlp_grad_workspace_bytes(desc, batch) bytes, 256-byte aligned.
+ *     Its contents on entry do not matter and are undefined on return.  Two calls that may run concurrently
+ *     (different streams) need different workspaces.
+ */
+typedef struct ulsnn_mlp_desc {
+    int n_in, n_hid, n_out;
+    const float *b1, *b2;
+    float *db1, *db2;
+    int accumulate;
+    int operand_dtype;
+    void *workspace;
+    size_t workspace_bytes;
+    void *hip_stream;
+} ulsnn_mlp_desc;
+
+/* Bytes of workspace ulsnn_mlp_grad needs for this network and batch (0 if desc is NULL or invalid).
+ * Host-only computation; non-decreasing in batch and constant above an internal slab size. */
+size_t ulsnn_mlp_grad_workspace_bytes(const ulsnn_mlp_desc *desc, int batch);
+
+/*
+ * Loss and gradient of the one-hidden-layer MLP over `batch` patterns (section 4.2):
+ *
+ *     H   = tanh(X W1 + 1 b1^T)                         hidden activations        [batch x n_hid]
+ *     Z   = H W2 + 1 b2^T                               output pre-activations    [batch x n_out]
+ *     P   = row softmax of Z;   loss = sum_r -ln P[r][labels[r]]
+ *     dO  = P - onehot(labels)                          output delta (the role of the paper's Y_Delta)
+ *     dW2 = H^T dO,  db2 = 1^T dO                       (the paper's grad_ho, transposed layout)
+ *     dA1 = (dO W2^T) ** (1 - H ** H)                   hidden delta (the paper's H_Delta; ** elementwise)
+ *     dW1 = X^T dA1, db1 = 1^T dA1                      (the paper's grad_ih, transposed layout)
+ *
+ *   Loss and gradients are sums over the patterns, not means.  The paper's own output stage (tanh outputs,
+ *   squared error against a dense target matrix) is replaced by softmax / cross-entropy against integer labels.
+ *   Counts batch * (4 n_in n_hid + 6 n_hid n_out) floating-point operations (section 6.2).
+ *
+ *   W1, W2, X [batch x n_in, dense row-major]: const device fp32.  labels[batch]: device int32; a label
+ *   outside [0, n_out) marks a pattern that is ignored (zero delta, nothing added to the loss).
+ *   dW1 [n_in x n_hid], dW2 [n_hid x n_out]: device fp32, dense.  loss: ONE device float.
+ *   batch == 0 is valid: with accumulate == 0 the outputs are zeroed, with accumulate == 1 nothing changes.
+ *   Large batches are processed in slabs of patterns internally; results are deterministic (no atomics):
+ *   the same call on the same data gives the same bits.
+ */
+int ulsnn_mlp_grad(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X,
+                   const int32_t *labels, int batch, float *dW1, float *dW2, float *loss);
+
+/*
+ * Gradient over a whole training set held in device memory, taken `chunk` patterns at a time and summed
+ * (section 4.3: additive over patterns; section 6.2: each processor steps through its patterns a fixed
+ * number at a time).  Equivalent to ulsnn_mlp_grad on patterns [0, chunk), then with accumulate = 1 on
+ * [chunk, 2 chunk), ... ; desc->accumulate applies to the first chunk.  The workspace must satisfy
+ * ulsnn_mlp_grad_workspace_bytes(desc, min(chunk, n_patterns)).  chunk < 1 is ULSNN_ERR_DIM.
+ * n_patterns is 64-bit: X may hold more than 2^31 elements.
+ */
+int ulsnn_mlp_grad_epoch(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X,
+                         const int32_t *labels, int64_t n_patterns, int chunk, float *dW1, float *dW2,
+                         float *loss);
+
+/*
+ * Diagnostic form of ulsnn_mlp_grad for measurement: the same work on the same kernels, with a HIP event
+ * recorded on the stream at each stage boundary.  The call WAITS for the stream to finish and writes the
+ * elapsed milliseconds of the ULSNN_MLP_STAGES stages to the HOST array stage_ms:
+ *   0 hidden layer (H)   1 output layer (Z)   2 softmax, cross-entropy, output delta, loss sum
+ *   3 dW2 = H^T dO       4 db2                5 hidden delta (dA1)      6 dW1 = X^T dA1      7 db1
+ * (section 4.2 names the products; stages 4 and 7 are empty without biases).  Only batches that fit one
+ * internal pass are accepted (1 <= batch <= 16384), otherwise ULSNN_ERR_UNSUPPORTED.  Creates and destroys
+ * HIP events; allocates no device memory.
+ */
+#define ULSNN_MLP_STAGES 8
+int ulsnn_mlp_grad_timed(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X,
+                         const int32_t *labels, int batch, float *dW1, float *dW2, float *loss,
+                         float *stage_ms);
+
+/* Counting conventions (host-only): 2mnk (section 3.1) and batch*(4 n_in n_hid + 6 n_hid n_out) (section 6.2). */
+double ulsnn_sgemm_flops(int m, int n, int k);
+double ulsnn_mlp_grad_flops(int n_in, int n_hid, int n_out, int64_t batch);
+
+/* Human-readable name of a status code (static storage; never NULL). */
+const char *ulsnn_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int ulsnn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ULSNN_H */

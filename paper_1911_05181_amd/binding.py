@@ -1,0 +1,213 @@
+"""ctypes binding of libulsnn.so: same names as the C entry points, argument marshalling only.
+
+There is no fallback: if the library has not been built, or a call returns an error status, an exception is
+raised.  Tensors must live on the GPU (their data_ptr() is handed to the library as a device pointer).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libulsnn.so"
+_lib = None
+
+
+class UlsnnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class _MlpDesc(C.Structure):
+    _fields_ = [("n_in", C.c_int), ("n_hid", C.c_int), ("n_out", C.c_int),
+                ("b1", C.c_void_p), ("b2", C.c_void_p), ("db1", C.c_void_p), ("db2", C.c_void_p),
+                ("accumulate", C.c_int), ("operand_dtype", C.c_int),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("hip_stream", C.c_void_p)]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def load():
+    """Load the shared library (built in-tree by paper_1911_05181_amd/build.py).  Fails loudly if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_1911_05181_amd.build` "
+                          f"(or __graft_entry__.build()); there is no fallback path")
+    L = C.CDLL(path)
+    vp, i, f = C.c_void_p, C.c_int, C.c_float
+    L.ulsnn_sgemm.argtypes = [C.c_char, C.c_char, i, i, i, f, vp, i, vp, i, f, vp, i, vp]
+    L.ulsnn_sgemm.restype = i
+    L.ulsnn_mlp_grad_workspace_bytes.argtypes = [C.POINTER(_MlpDesc), i]
+    L.ulsnn_mlp_grad_workspace_bytes.restype = C.c_size_t
+    L.ulsnn_mlp_grad.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, i, vp, vp, vp]
+    L.ulsnn_mlp_grad.restype = i
+    L.ulsnn_mlp_grad_epoch.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, C.c_int64, i, vp, vp, vp]
+    L.ulsnn_mlp_grad_epoch.restype = i
+    L.ulsnn_mlp_grad_timed.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, i, vp, vp, vp, C.POINTER(C.c_float)]
+    L.ulsnn_mlp_grad_timed.restype = i
+    L.ulsnn_sgemm_flops.argtypes = [i, i, i]
+    L.ulsnn_sgemm_flops.restype = C.c_double
+    L.ulsnn_mlp_grad_flops.argtypes = [i, i, i, C.c_int64]
+    L.ulsnn_mlp_grad_flops.restype = C.c_double
+    L.ulsnn_status_string.argtypes = [i]
+    L.ulsnn_status_string.restype = C.c_char_p
+    L.ulsnn_version.argtypes = []
+    L.ulsnn_version.restype = i
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return load().ulsnn_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(load().ulsnn_version())
+
+
+def sgemm_flops(m: int, n: int, k: int) -> float:
+    return float(load().ulsnn_sgemm_flops(m, n, k))
+
+
+def mlp_grad_flops(n_in: int, n_hid: int, n_out: int, batch: int) -> float:
+    return float(load().ulsnn_mlp_grad_flops(n_in, n_hid, n_out, batch))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _dev_f32(t: torch.Tensor, name: str):
+    if not (t.is_cuda and t.dtype == torch.float32):
+        raise TypeError(f"{name} must be a float32 tensor on the GPU")
+
+
+def sgemm(transa: str, transb: str, m: int, n: int, k: int, alpha: float, A: torch.Tensor, lda: int,
+          B: torch.Tensor, ldb: int, beta: float, Cmat: torch.Tensor, ldc: int, stream=None) -> None:
+    """C = alpha*op(A)*op(B) + beta*C in place on the GPU (row-major, BLAS SGEMM argument order)."""
+    for t, nm in ((A, "A"), (B, "B"), (Cmat, "C")):
+        if t is not None:
+            _dev_f32(t, nm)
+    rc = load().ulsnn_sgemm(transa.encode()[:1], transb.encode()[:1], m, n, k, alpha, _ptr(A), lda, _ptr(B), ldb,
+                            beta, _ptr(Cmat), ldc, _stream(stream))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_sgemm")
+
+
+def _desc(n_in, n_hid, n_out, b1, b2, db1, db2, accumulate, workspace, stream, operand_dtype=0) -> _MlpDesc:
+    d = _MlpDesc()
+    d.n_in, d.n_hid, d.n_out = n_in, n_hid, n_out
+    d.b1, d.b2, d.db1, d.db2 = _ptr(b1), _ptr(b2), _ptr(db1), _ptr(db2)
+    d.accumulate = int(accumulate)
+    d.operand_dtype = operand_dtype
+    d.workspace = _ptr(workspace)
+    d.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    d.hip_stream = _stream(stream) if torch.cuda.is_available() else None
+    return d
+
+
+def mlp_grad_workspace_bytes(n_in: int, n_hid: int, n_out: int, batch: int) -> int:
+    d = _MlpDesc()
+    d.n_in, d.n_hid, d.n_out = n_in, n_hid, n_out
+    return int(load().ulsnn_mlp_grad_workspace_bytes(C.byref(d), batch))
+
+
+@dataclass
+class MlpGradResult:
+    dW1: torch.Tensor
+    dW2: torch.Tensor
+    loss: torch.Tensor            # one float on the device
+    db1: Optional[torch.Tensor] = None
+    db2: Optional[torch.Tensor] = None
+
+
+def _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate):
+    _dev_f32(W1, "W1"), _dev_f32(W2, "W2"), _dev_f32(X, "X")
+    if not (labels.is_cuda and labels.dtype == torch.int32):
+        raise TypeError("labels must be an int32 tensor on the GPU")
+    for t in (W1, W2, X, labels):
+        if not t.is_contiguous():
+            raise ValueError("W1, W2, X and labels must be dense (contiguous)")
+    n_in, n_hid = W1.shape
+    n_out = W2.shape[1]
+    if W2.shape[0] != n_hid or X.shape[1] != n_in or labels.shape[0] != X.shape[0]:
+        raise ValueError("shape mismatch between W1, W2, X and labels")
+    if (b1 is None) != (b2 is None):
+        raise ValueError("give both biases or neither")
+    if out is None:
+        if accumulate:
+            raise ValueError("accumulate=True needs the tensors to add to (out=...)")
+        dev = W1.device
+        out = MlpGradResult(torch.empty_like(W1), torch.empty_like(W2), torch.empty(1, device=dev),
+                            None if b1 is None else torch.empty_like(b1),
+                            None if b2 is None else torch.empty_like(b2))
+    return n_in, n_hid, n_out, out
+
+
+def mlp_grad(W1, W2, X, labels, b1=None, b2=None, *, out: Optional[MlpGradResult] = None, accumulate=False,
+             workspace: Optional[torch.Tensor] = None, stream=None) -> MlpGradResult:
+    """Loss and gradient of the MLP summed over the rows of X (ulsnn_mlp_grad).  Asynchronous on the stream."""
+    n_in, n_hid, n_out, out = _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate)
+    batch = X.shape[0]
+    if workspace is None:
+        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
+    d = _desc(n_in, n_hid, n_out, b1, b2, out.db1, out.db2, accumulate, workspace, stream)
+    rc = load().ulsnn_mlp_grad(C.byref(d), _ptr(W1), _ptr(W2), _ptr(X), _ptr(labels), batch, _ptr(out.dW1),
+                               _ptr(out.dW2), _ptr(out.loss))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_mlp_grad")
+    return out
+
+
+MLP_STAGES = ("hidden_layer", "output_layer", "softmax_ce", "dW2", "db2", "hidden_delta", "dW1", "db1")
+
+
+def mlp_grad_timed(W1, W2, X, labels, b1=None, b2=None, *, out: Optional[MlpGradResult] = None, accumulate=False,
+                   workspace: Optional[torch.Tensor] = None, stream=None):
+    """ulsnn_mlp_grad_timed: the same work with HIP events at the stage boundaries.  Synchronises the stream.
+    Returns (result, {stage name: milliseconds})."""
+    n_in, n_hid, n_out, out = _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate)
+    batch = X.shape[0]
+    if workspace is None:
+        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
+    d = _desc(n_in, n_hid, n_out, b1, b2, out.db1, out.db2, accumulate, workspace, stream)
+    ms = (C.c_float * len(MLP_STAGES))()
+    rc = load().ulsnn_mlp_grad_timed(C.byref(d), _ptr(W1), _ptr(W2), _ptr(X), _ptr(labels), batch, _ptr(out.dW1),
+                                     _ptr(out.dW2), _ptr(out.loss), ms)
+    if rc:
+        raise UlsnnError(rc, "ulsnn_mlp_grad_timed")
+    return out, dict(zip(MLP_STAGES, (float(v) for v in ms)))
+
+
+def mlp_grad_epoch(W1, W2, X, labels, chunk: int, b1=None, b2=None, *, out: Optional[MlpGradResult] = None,
+                   accumulate=False, workspace: Optional[torch.Tensor] = None, stream=None) -> MlpGradResult:
+    """Gradient over all rows of X taken `chunk` patterns at a time and summed (ulsnn_mlp_grad_epoch)."""
+    n_in, n_hid, n_out, out = _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate)
+    n = X.shape[0]
+    if workspace is None:
+        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, min(max(chunk, 1), max(n, 1)))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
+    d = _desc(n_in, n_hid, n_out, b1, b2, out.db1, out.db2, accumulate, workspace, stream)
+    rc = load().ulsnn_mlp_grad_epoch(C.byref(d), _ptr(W1), _ptr(W2), _ptr(X), _ptr(labels), n, chunk,
+                                     _ptr(out.dW1), _ptr(out.dW2), _ptr(out.loss))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_mlp_grad_epoch")
+    return out

@@ -1,0 +1,299 @@
+// fp32 GEMM on the gfx950 matrix cores: C = epilogue(op(A) * op(B)).
+//
+// One workgroup computes a BM x BN tile of C.  It is WM x WN wavefronts of 64 lanes; each wavefront owns a
+// (BM/WM) x (BN/WN) sub-tile built from 32 x 32 accumulator blocks of v_mfma_f32_32x32x2_f32.  The k loop runs
+// in steps of BK: the next A and B panels are fetched from global memory into registers while the matrix cores
+// work on the current panels in LDS (two LDS stages, one barrier per step).
+//
+// Operand layouts.  An operand is "KC" when k is the contiguous direction of its storage (A for op = N,
+// B for op = T) and "MC" when the row/column index of C is (A for op = T, B for op = N).  Both are fetched
+// with 16-byte loads along their contiguous direction and stored to LDS the same way round, so transposition
+// costs nothing: it only changes which LDS addresses a lane reads.  The 32x32x2 instruction takes, per lane,
+// ONE element of A (row lane%32, k = lane/32) and ONE of B (column lane%32, same k).  Because a sum over k does
+// not care about the order of its terms, lane half h = lane/32 is given k = 8*s + 4*h + t in the t-th
+// instruction of the s-th group of four: a KC operand then needs a single 16-byte LDS read per 32 rows per
+// group, an MC operand four 4-byte reads.
+//
+// Edges.  Rows/columns beyond M/N are fetched from a clamped (valid) address or zero filled and never stored;
+// k beyond the end of the workgroup's k range is zero filled.  Pointers need only 4-byte alignment.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+namespace ulsnn {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+enum Epilogue {
+    EPI_AXPBY = 0,      // C = alpha*acc + beta*C   (beta == 0: C not read)
+    EPI_PARTIAL = 1,    // split-k partial: P[z] = acc (dense, ld = N)
+    EPI_BIAS_TANH = 2,  // C = tanh(acc + bias[j])
+    EPI_BIAS = 3,       // C = acc + bias[j]
+    EPI_TANHGRAD = 4    // C = acc * (1 - aux[i][j]^2)
+};
+
+struct GemmArgs {
+    const float *A, *B;
+    float *C;
+    int M, N, K;
+    int lda, ldb, ldc;
+    float alpha, beta;
+    const float *bias;   // EPI_BIAS_TANH / EPI_BIAS, may be null (no bias)
+    const float *aux;    // EPI_TANHGRAD: the tanh outputs, same shape as C
+    int ldaux;
+    int kchunk;          // k range handled per blockIdx.y (multiple of BK); >= K when there is no split
+    int tiles_m, tiles_n;
+    size_t partial_stride;  // EPI_PARTIAL: elements between consecutive partial results
+};
+
+template <int BM_, int BN_, int BK_, int WM_, int WN_>
+struct TileCfg {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
+    static constexpr int THREADS = WM * WN * 64;
+    static constexpr int WTM = BM / WM, WTN = BN / WN;   // wavefront sub-tile
+    static constexpr int TM = WTM / 32, TN = WTN / 32;   // 32x32 accumulator blocks per wavefront
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % 8 == 0, "tile shape");
+};
+
+// LDS footprint (floats) of one stage of one operand panel with R rows/columns of C
+template <bool KC, int R, int BK>
+struct Panel {
+    static constexpr int LD = KC ? (BK + 4) : (R + 8);       // padded row length
+    static constexpr int SIZE = KC ? R * LD : BK * LD;
+};
+
+__device__ __forceinline__ floatx4 load4_any_align(const float *p)
+{
+    floatx4 v;
+    __builtin_memcpy(&v, p, 16);   // 4-byte aligned 16-byte load
+    return v;
+}
+
+// Fetch this thread's share of a panel (rows r0.., k from k0, valid k < kend) into registers.
+template <bool KC, int R, int BK, int THREADS, int NV>
+__device__ __forceinline__ void panel_fetch(floatx4 (&reg)[NV], const float *__restrict__ P, int ld, int r0,
+                                            int rmax, int k0, int kend, int tid)
+{
+    constexpr int TOTAL = R * BK / 4;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int f = tid + v * THREADS;
+        floatx4 val = {0.f, 0.f, 0.f, 0.f};
+        if (TOTAL % THREADS == 0 || f < TOTAL) {
+            if (KC) {
+                const int row = f / (BK / 4), kq = (f % (BK / 4)) * 4;
+                int gr = r0 + row;
+                gr = gr < rmax ? gr : rmax - 1;                       // clamp: value unused beyond the edge
+                const int gk = k0 + kq;
+                const float *src = P + (size_t)gr * ld + gk;
+                if (gk + 3 < kend) {
+                    val = load4_any_align(src);
+                } else {
+                    if (gk + 0 < kend) val.x = src[0];
+                    if (gk + 1 < kend) val.y = src[1];
+                    if (gk + 2 < kend) val.z = src[2];
+                }
+            } else {
+                const int krow = f / (R / 4), rq = (f % (R / 4)) * 4;
+                const int gk = k0 + krow, gr = r0 + rq;
+                if (gk < kend) {
+                    const float *src = P + (size_t)gk * ld + gr;
+                    if (gr + 3 < rmax) {
+                        val = load4_any_align(src);
+                    } else {
+                        if (gr + 0 < rmax) val.x = src[0];
+                        if (gr + 1 < rmax) val.y = src[1];
+                        if (gr + 2 < rmax) val.z = src[2];
+                    }
+                }
+            }
+        }
+        reg[v] = val;
+    }
+}
+
+template <bool KC, int R, int BK, int THREADS, int NV>
+__device__ __forceinline__ void panel_store(float *lds, const floatx4 (&reg)[NV], int tid)
+{
+    constexpr int TOTAL = R * BK / 4;
+    constexpr int LD = Panel<KC, R, BK>::LD;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int f = tid + v * THREADS;
+        if (TOTAL % THREADS == 0 || f < TOTAL) {
+            int off;
+            if (KC) off = (f / (BK / 4)) * LD + (f % (BK / 4)) * 4;
+            else off = (f / (R / 4)) * LD + (f % (R / 4)) * 4;
+            *reinterpret_cast<floatx4 *>(lds + off) = reg[v];
+        }
+    }
+}
+
+// Operand values of one group of four 32x32x2 steps (k = 8*s + 4*h + t, t = 0..3) for 32 rows starting at `row`.
+template <bool KC, int R, int BK>
+__device__ __forceinline__ floatx4 panel_read(const float *lds, int row, int s, int l32, int h)
+{
+    constexpr int LD = Panel<KC, R, BK>::LD;
+    if (KC) {
+        return *reinterpret_cast<const floatx4 *>(lds + (row + l32) * LD + s * 8 + h * 4);
+    } else {
+        const float *p = lds + (s * 8 + h * 4) * LD + row + l32;
+        floatx4 v;
+        v.x = p[0];
+        v.y = p[LD];
+        v.z = p[2 * LD];
+        v.w = p[3 * LD];
+        return v;
+    }
+}
+
+// Map the hardware workgroup id to a tile.  Consecutive ids are spread round-robin over the 8 XCDs (each with
+// its own L2), so each XCD is given a contiguous range of tiles, and inside it tiles are walked in groups of
+// GROUP_M tile rows so that the A and B panels a group touches stay in that L2.
+__device__ __forceinline__ void tile_of_workgroup(int pid, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    constexpr int XCDS = 8, GROUP_M = 8;
+    const int nt = tiles_m * tiles_n;
+    const int q = nt / XCDS, rem = nt % XCDS;
+    const int xcd = pid % XCDS, loc = pid / XCDS;
+    const int lid = xcd * q + (xcd < rem ? xcd : rem) + loc;
+    const int group = GROUP_M * tiles_n;
+    const int gid = lid / group;
+    const int first_m = gid * GROUP_M;
+    const int gsz = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
+    tm = first_m + (lid % group) % gsz;
+    tn = (lid % group) / gsz;
+}
+
+__device__ __forceinline__ float tanh_f32(float x)
+{
+    // tanh(x) = sign(x) * (1 - 2/(exp(2|x|)+1)); for small |x| the odd series avoids the cancellation
+    const float ax = fabsf(x);
+    float r;
+    if (ax < 0.25f) {
+        const float x2 = x * x;
+        // x - x^3/3 + 2x^5/15 - 17x^7/315 + 62x^9/2835
+        r = ax * (1.0f + x2 * (-0.33333333f + x2 * (0.13333333f + x2 * (-0.053968254f + x2 * 0.021869488f))));
+    } else {
+        const float e = __expf(2.0f * ax);
+        r = 1.0f - 2.0f / (e + 1.0f);
+    }
+    return copysignf(r, x);
+}
+
+template <class Cfg, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(const GemmArgs g)
+{
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, THREADS = Cfg::THREADS;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN;
+    using PA = Panel<A_KC, BM, BK>;
+    using PB = Panel<B_KC, BN, BK>;
+    constexpr int NVA = (BM * BK / 4 + THREADS - 1) / THREADS;
+    constexpr int NVB = (BN * BK / 4 + THREADS - 1) / THREADS;
+
+    __shared__ __attribute__((aligned(16))) float lds_a[2][PA::SIZE];
+    __shared__ __attribute__((aligned(16))) float lds_b[2][PB::SIZE];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
+
+    int tile_m, tile_n;
+    tile_of_workgroup(blockIdx.x, g.tiles_m, g.tiles_n, tile_m, tile_n);
+    const int i0 = tile_m * BM, j0 = tile_n * BN;
+    const int z = blockIdx.y;
+    const int kbeg = z * g.kchunk;
+    const int kend = (kbeg + g.kchunk < g.K) ? kbeg + g.kchunk : g.K;
+    const int nkb = (kend - kbeg + BK - 1) / BK;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    floatx4 ra[NVA], rb[NVB];
+    if (nkb > 0) {
+        panel_fetch<A_KC, BM, BK, THREADS, NVA>(ra, g.A, g.lda, i0, g.M, kbeg, kend, tid);
+        panel_fetch<B_KC, BN, BK, THREADS, NVB>(rb, g.B, g.ldb, j0, g.N, kbeg, kend, tid);
+        panel_store<A_KC, BM, BK, THREADS, NVA>(lds_a[0], ra, tid);
+        panel_store<B_KC, BN, BK, THREADS, NVB>(lds_b[0], rb, tid);
+    }
+    __syncthreads();
+
+    for (int kb = 0; kb < nkb; ++kb) {
+        const int cur = kb & 1;
+        const bool more = kb + 1 < nkb;
+        if (more) {
+            const int k0 = kbeg + (kb + 1) * BK;
+            panel_fetch<A_KC, BM, BK, THREADS, NVA>(ra, g.A, g.lda, i0, g.M, k0, kend, tid);
+            panel_fetch<B_KC, BN, BK, THREADS, NVB>(rb, g.B, g.ldb, j0, g.N, k0, kend, tid);
+        }
+        const float *la = lds_a[cur], *lb = lds_b[cur];
+#pragma unroll
+        for (int s = 0; s < BK / 8; ++s) {
+            floatx4 a[TM], b[TN];
+#pragma unroll
+            for (int x = 0; x < TM; ++x) a[x] = panel_read<A_KC, BM, BK>(la, wm * Cfg::WTM + x * 32, s, l32, h);
+#pragma unroll
+            for (int y = 0; y < TN; ++y) b[y] = panel_read<B_KC, BN, BK>(lb, wn * Cfg::WTN + y * 32, s, l32, h);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int x = 0; x < TM; ++x)
+#pragma unroll
+                    for (int y = 0; y < TN; ++y)
+                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[x][t], b[y][t], acc[x][y], 0, 0, 0);
+        }
+        if (more) {
+            panel_store<A_KC, BM, BK, THREADS, NVA>(lds_a[cur ^ 1], ra, tid);
+            panel_store<B_KC, BN, BK, THREADS, NVB>(lds_b[cur ^ 1], rb, tid);
+        }
+        __syncthreads();
+    }
+
+    // Epilogue.  Accumulator register r of a 32x32 block holds row 8*(r/4) + 4*h + r%4, column lane%32.
+    float *Cout = g.C;
+    int ldc = g.ldc;
+    if (EPI == EPI_PARTIAL) {
+        Cout = g.C + (size_t)z * g.partial_stride;
+        ldc = g.N;
+    }
+#pragma unroll
+    for (int y = 0; y < TN; ++y) {
+        const int j = j0 + wn * Cfg::WTN + y * 32 + l32;
+        if (j >= g.N) continue;
+        float bias = 0.f;
+        if ((EPI == EPI_BIAS_TANH || EPI == EPI_BIAS) && g.bias) bias = g.bias[j];
+#pragma unroll
+        for (int x = 0; x < TM; ++x) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = i0 + wm * Cfg::WTM + x * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                if (i >= g.M) continue;
+                const float v = acc[x][y][r];
+                float *dst = Cout + (size_t)i * ldc + j;
+                if (EPI == EPI_AXPBY) {
+                    float out = g.alpha * v;
+                    if (g.beta != 0.f) out += g.beta * *dst;
+                    *dst = out;
+                } else if (EPI == EPI_PARTIAL) {
+                    *dst = v;
+                } else if (EPI == EPI_BIAS_TANH) {
+                    *dst = tanh_f32(v + bias);
+                } else if (EPI == EPI_BIAS) {
+                    *dst = v + bias;
+                } else {
+                    const float hv = g.aux[(size_t)i * g.ldaux + j];
+                    *dst = v * (1.0f - hv * hv);
+                }
+            }
+        }
+    }
+}
+
+}  // namespace ulsnn

@@ -1,0 +1,121 @@
+"""Host-side checks of the C ABI that need no GPU: every declared symbol is exported, and argument
+validation (which runs before any HIP call) returns the documented status codes."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_1911_05181_amd as ulsnn
+from paper_1911_05181_amd.binding import _MlpDesc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, E_NULL, E_TRANS, E_DIM, E_LD, E_WS, E_UNSUP, E_HIP = range(8)
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "ulsnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ulsnn_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = ulsnn.load()
+    names = _declared_functions()
+    assert {"ulsnn_sgemm", "ulsnn_mlp_grad", "ulsnn_mlp_grad_epoch", "ulsnn_mlp_grad_workspace_bytes",
+            "ulsnn_status_string", "ulsnn_version", "ulsnn_sgemm_flops", "ulsnn_mlp_grad_flops"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings_and_version():
+    assert ulsnn.version() >= 100
+    seen = {ulsnn.status_string(s) for s in range(8)}
+    assert len(seen) == 8 and ulsnn.status_string(99) == "unknown status"
+
+
+def test_counting_conventions_match_the_paper():
+    # section 3.1: 2MNK; section 6.2: n_p (4 n_i n_h + 6 n_h n_o); section 5.1 network
+    assert ulsnn.sgemm_flops(320, 320, 320) == 2 * 320**3
+    assert ulsnn.mlp_grad_flops(400, 480, 3203, 1) == 9_992_640
+    assert int(ulsnn.mlp_grad_flops(400, 480, 3203, 9_264_000) / 1e12) == 92
+
+
+def _sgemm(ta, tb, m, n, k, lda, ldb, ldc, A=1, B=1, Cm=1, alpha=1.0):
+    # pointers are never dereferenced on these paths: every call below must be rejected (or be a no-op)
+    L = ulsnn.load()
+    p = lambda v: C.c_void_p(0x1000 if v else 0)
+    return L.ulsnn_sgemm(ta.encode(), tb.encode(), m, n, k, alpha, p(A), lda, p(B), ldb, 0.0, p(Cm), ldc, None)
+
+
+def test_sgemm_argument_errors():
+    assert _sgemm("X", "N", 4, 4, 4, 4, 4, 4) == E_TRANS
+    assert _sgemm("N", "Q", 4, 4, 4, 4, 4, 4) == E_TRANS
+    assert _sgemm("N", "N", -1, 4, 4, 4, 4, 4) == E_DIM
+    assert _sgemm("N", "N", 4, -1, 4, 4, 4, 4) == E_DIM
+    assert _sgemm("N", "N", 4, 4, -1, 4, 4, 4) == E_DIM
+    assert _sgemm("N", "N", 4, 5, 6, 5, 5, 5) == E_LD      # lda < k
+    assert _sgemm("T", "N", 4, 5, 6, 3, 5, 5) == E_LD      # A stored k x m: lda < m
+    assert _sgemm("N", "N", 4, 5, 6, 6, 4, 5) == E_LD      # ldb < n
+    assert _sgemm("N", "T", 4, 5, 6, 6, 5, 5) == E_LD      # B stored n x k: ldb < k
+    assert _sgemm("N", "N", 4, 5, 6, 6, 5, 4) == E_LD      # ldc < n
+    assert _sgemm("N", "N", 0, 5, 6, 6, 5, 5) == OK        # m == 0: nothing to do, no launch
+    assert _sgemm("N", "N", 4, 0, 6, 6, 1, 1) == OK
+    assert _sgemm("N", "N", 4, 5, 6, 6, 5, 5, Cm=0) == E_NULL
+    assert _sgemm("N", "N", 4, 5, 6, 6, 5, 5, A=0) == E_NULL
+    assert _sgemm("N", "N", 4, 5, 6, 6, 5, 5, B=0) == E_NULL
+    for t in "NnTtCc":
+        assert _sgemm(t, t, 0, 0, 0, 1, 1, 1) == OK
+
+
+def _desc(**kw):
+    d = _MlpDesc()
+    d.n_in, d.n_hid, d.n_out = 400, 480, 3203
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def _grad(d, W1=1, W2=1, X=1, y=1, batch=8, dW1=1, dW2=1, loss=1):
+    L = ulsnn.load()
+    p = lambda v: C.c_void_p(0x1000 if v else 0)
+    return L.ulsnn_mlp_grad(C.byref(d) if d is not None else None, p(W1), p(W2), p(X), p(y), batch, p(dW1),
+                            p(dW2), p(loss))
+
+
+def test_mlp_grad_argument_errors():
+    assert _grad(None) == E_NULL
+    assert _grad(_desc(n_hid=0)) == E_DIM
+    assert _grad(_desc(), batch=-1) == E_DIM
+    for missing in ("W1", "W2", "X", "y", "dW1", "dW2", "loss"):
+        assert _grad(_desc(), **{missing: 0}) == E_NULL
+    assert _grad(_desc(b1=0x1000)) == E_NULL                     # biases: all four or none
+    assert _grad(_desc(b1=0x1000, b2=0x1000, db1=0x1000)) == E_NULL
+    assert _grad(_desc(operand_dtype=1)) == E_UNSUP              # bf16 storage is reserved
+    assert _grad(_desc(accumulate=2)) == E_UNSUP
+    assert _grad(_desc()) == E_WS                                # no workspace
+    need = ulsnn.mlp_grad_workspace_bytes(400, 480, 3203, 8)
+    assert _grad(_desc(workspace=0x1000, workspace_bytes=need - 1)) == E_WS
+    assert _grad(_desc(workspace=0x1010, workspace_bytes=need)) == E_WS      # not 256-byte aligned
+    L = ulsnn.load()
+    p = C.c_void_p(0x1000)
+    d = _desc(workspace=0x1000, workspace_bytes=1 << 40)
+    assert L.ulsnn_mlp_grad_epoch(C.byref(d), p, p, p, p, 100, 0, p, p, p) == E_DIM
+    assert L.ulsnn_mlp_grad_epoch(C.byref(_desc()), p, p, p, p, 100, 10, p, p, p) == E_WS
+
+
+def test_workspace_query():
+    w = ulsnn.mlp_grad_workspace_bytes
+    assert w(400, 480, 3203, 0) == 0 and w(0, 480, 3203, 16) == 0
+    sizes = [w(400, 480, 3203, b) for b in (1, 100, 4096, 16384, 16385, 262144, 9_000_000)]
+    assert all(a <= b for a, b in zip(sizes, sizes[1:]))         # non-decreasing in batch
+    assert sizes[-1] == sizes[-2] == sizes[-3]                   # constant above the slab size
+    assert sizes[2] >= 4096 * (3203 + 2 * 480) * 4               # holds Z, H and dA1 of the batch
+    assert sizes[-1] < 1 << 30                                   # and stays modest for any batch
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    a = torch.zeros(4, 4)
+    with pytest.raises(TypeError):
+        ulsnn.sgemm("N", "N", 4, 4, 4, 1.0, a, 4, a, 4, 0.0, a, 4)

@@ -1,0 +1,167 @@
+"""Parity of ulsnn_mlp_grad / ulsnn_mlp_grad_epoch (HIP, through the C ABI) against the CPU oracle.
+
+Bar (task statement): relative L2 error <= 1e-4 per gradient tensor against the double-precision oracle fed the
+same fp32 inputs; loss within 1e-5 relative.  fp32 products summed over up to 4096..40000 patterns carry a
+relative error of a few 1e-7..1e-6, so observed values (printed) should sit near 1e-6.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1911_05181_amd as ulsnn
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL_GRAD, TOL_LOSS = 1e-4, 1e-5
+
+
+def _rel(a, b):
+    a = a.astype(np.float64)
+    nb = np.linalg.norm(b)
+    return np.linalg.norm(a - b) / nb if nb > 0 else np.linalg.norm(a)
+
+
+def _problem(shape, seed, batch, random_biases=False, first=0):
+    W1, W2, b1, b2 = si.mlp_weights(shape, seed)
+    if shape.biases and random_biases:
+        b1, b2 = si.random_biases(shape, seed, 0.2)
+    X, y = si.mlp_patterns(shape, seed, first, batch)
+    return W1, W2, b1, b2, X, y
+
+
+def _np(t):
+    return None if t is None else t.numpy()
+
+
+def _dev(t):
+    return None if t is None else t.to(DEV)
+
+
+def _compare(res, ref, tag):
+    torch.cuda.synchronize()
+    worst = 0.0
+    for name in ("dW1", "dW2", "db1", "db2"):
+        g, r = getattr(res, name), getattr(ref, name)
+        if r is None:
+            continue
+        e = _rel(g.cpu().numpy(), r)
+        worst = max(worst, e)
+        assert e <= TOL_GRAD, (tag, name, e)
+    le = abs(res.loss.item() - ref.loss) / max(abs(ref.loss), 1e-30)
+    assert le <= TOL_LOSS, (tag, "loss", le)
+    print(f"{tag}: worst gradient rel-L2 {worst:.2e}, loss rel {le:.2e}")
+
+
+def _gpu_grad(W1, W2, b1, b2, X, y, **kw):
+    return ulsnn.mlp_grad(_dev(W1), _dev(W2), _dev(X), _dev(y), _dev(b1), _dev(b2), **kw)
+
+
+def _oracle_grad(W1, W2, b1, b2, X, y):
+    return oracle.mlp_grad(_np(W1), _np(W2), _np(X), _np(y), _np(b1), _np(b2))
+
+
+def test_small_net_with_biases():
+    """64-32-10, batch 256, seed 0: the small configuration (zero biases as specified, then random ones)."""
+    for rb in (False, True):
+        p = _problem(si.MLP_SMALL, 0, 256, random_biases=rb)
+        _compare(_gpu_grad(*p), _oracle_grad(*p), f"64-32-10 B=256 random_biases={rb}")
+
+
+@pytest.mark.parametrize("n_in,n_hid,n_out,batch,biases", [
+    (100, 130, 259, 300, True),      # every dimension ragged against the 128/64/32 tiles
+    (17, 33, 5, 1, True),            # a single pattern
+    (400, 480, 3203, 257, False),    # the paper's network, a batch with a ragged tail
+    (64, 32, 4500, 37, True),        # rows too long for the register softmax
+    (33, 7, 2, 1000, False),
+])
+def test_ragged_shapes(n_in, n_hid, n_out, batch, biases):
+    p = _problem(si.MlpShape(n_in, n_hid, n_out, biases), 5, batch, random_biases=True)
+    _compare(_gpu_grad(*p), _oracle_grad(*p), f"{n_in}-{n_hid}-{n_out} B={batch}")
+
+
+def test_jocr_network_full_batch():
+    """400-480-3203 (the paper's network, section 6.1), batch 4096, seed 2: the benchmark workload, every
+    element of both gradients against the oracle."""
+    p = _problem(si.MLP_JOCR, 2, 4096)
+    ref = _oracle_grad(*p)
+    res = _gpu_grad(*p)
+    _compare(res, ref, "400-480-3203 B=4096")
+    again = _gpu_grad(*p)
+    torch.cuda.synchronize()
+    assert torch.equal(res.dW1, again.dW1) and torch.equal(res.dW2, again.dW2) and torch.equal(res.loss, again.loss)
+
+
+def test_empty_batch_and_accumulate():
+    shape = si.MlpShape(20, 12, 9, True)
+    W1, W2, b1, b2, X, y = _problem(shape, 7, 64, random_biases=True)
+    res = _gpu_grad(W1, W2, b1, b2, X[:0], y[:0])
+    torch.cuda.synchronize()
+    for t in (res.dW1, res.dW2, res.db1, res.db2, res.loss):
+        assert not t.any()
+    # accumulate: two halves added into the same tensors equal the whole (additivity, section 4.3)
+    out = _gpu_grad(W1, W2, b1, b2, X[:40], y[:40])
+    _gpu_grad(W1, W2, b1, b2, X[40:], y[40:], out=out, accumulate=True)
+    _gpu_grad(W1, W2, b1, b2, X[:0], y[:0], out=out, accumulate=True)        # adds nothing
+    _compare(out, _oracle_grad(W1, W2, b1, b2, X, y), "accumulate 40+24+0")
+
+
+def test_out_of_range_labels_are_ignored():
+    shape = si.MlpShape(30, 20, 11, True)
+    W1, W2, b1, b2, X, y = _problem(shape, 8, 50, random_biases=True)
+    y = y.clone()
+    y[3], y[17], y[49] = -1, 11, 1 << 20
+    _compare(_gpu_grad(W1, W2, b1, b2, X, y), _oracle_grad(W1, W2, b1, b2, X, y), "ignored labels")
+
+
+def test_closed_form_zero_output_weights():
+    shape = si.MLP_JOCR
+    W1, W2, _, _, X, y = _problem(shape, 2, 512)
+    res = _gpu_grad(W1, torch.zeros_like(W2), None, None, X, y)
+    torch.cuda.synchronize()
+    assert abs(res.loss.item() - 512 * math.log(3203)) <= 1e-5 * 512 * math.log(3203)   # B ln n_out
+    assert not res.dW1.any()                                                            # dH = dO * 0
+
+
+def test_chunked_epoch_matches_oracle_and_single_call():
+    """Epoch gradient over 3 chunks of 1024 + a tail of 300 patterns (the streaming path at reduced size)."""
+    n = 3 * 1024 + 300
+    p = _problem(si.MLP_JOCR, 2, n)
+    W1, W2, _, _, X, y = p
+    res = ulsnn.mlp_grad_epoch(_dev(W1), _dev(W2), _dev(X), _dev(y), 1024)
+    _compare(res, _oracle_grad(*p), "epoch 3x1024+300")
+    # a chunk larger than the data is a single call
+    one = ulsnn.mlp_grad_epoch(_dev(W1), _dev(W2), _dev(X), _dev(y), 1 << 20)
+    whole = _gpu_grad(*p)
+    torch.cuda.synchronize()
+    assert torch.equal(one.dW1, whole.dW1) and torch.equal(one.dW2, whole.dW2)
+
+
+def test_batch_larger_than_internal_slab():
+    """A batch that the library splits into several internal passes (small net so the oracle stays quick)."""
+    p = _problem(si.MLP_SMALL, 0, 40_000, random_biases=True)
+    _compare(_gpu_grad(*p), _oracle_grad(*p), "64-32-10 B=40000")
+
+
+def test_additivity_on_device():
+    p = _problem(si.MLP_JOCR, 2, 1500)
+    W1, W2, _, _, X, y = p
+    whole = _gpu_grad(*p)
+    a = _gpu_grad(W1, W2, None, None, X[:700], y[:700])
+    b = _gpu_grad(W1, W2, None, None, X[700:], y[700:])
+    torch.cuda.synchronize()
+    for name in ("dW1", "dW2"):
+        s = (getattr(a, name) + getattr(b, name)).cpu().numpy()
+        assert _rel(s, getattr(whole, name).cpu().numpy().astype(np.float64)) < 1e-5
+    assert abs(a.loss.item() + b.loss.item() - whole.loss.item()) < 1e-5 * whole.loss.item()
+
+
+def test_workspace_too_small_is_refused():
+    p = _problem(si.MLP_SMALL, 0, 256)
+    ws = torch.empty(1024, dtype=torch.uint8, device=DEV)
+    with pytest.raises(ulsnn.UlsnnError) as e:
+        _gpu_grad(*p, workspace=ws)
+    assert e.value.status == 5
