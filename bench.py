@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--no-sgemm]
+
+A step is one gradient of the 400-480-3203 network (the paper's network, section 6.1) over a batch of 4096
+synthetic patterns, through ulsnn_mlp_grad: every stage of the path (two forward products with their fused
+epilogues, softmax / cross-entropy / output delta, three backward products, loss).  Inputs are resident in HBM
+before the timed region.  Flops are counted with the paper's convention (section 6.2): batch * (4 n_i n_h +
+6 n_h n_o); elementwise and reduction work counts as zero.  The same run also times the standalone SGEMM at the
+square sizes of the second workload (reported under "sgemm").
+
+"roofline" describes the dominant kernel of the step: the matrix-core GEMM launch that takes the most time,
+timed live with HIP events recorded on the launch stream (ulsnn_mlp_grad_timed), against the MI355X fp32 matrix
+peak of 157.3 TFLOP/s.  "cpu_baseline" is the CPU oracle (float arithmetic) timed on the host cores on the same
+workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3      # 256 CUs x 256 flop/clk/CU x 2.4 GHz
+METRIC = "fp32 GFLOP/s (% of MFMA FP32 peak); MLP gradient patterns/sec"
+BATCH = 4096
+SEED = 2
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-sgemm", action="store_true", help="skip the standalone SGEMM sweep")
+    ap.add_argument("--sgemm-sizes", type=int, nargs="*", default=[256, 1024, 4096, 8192])
+    return ap.parse_args()
+
+
+def bench_sgemm(ulsnn, si, torch, sizes):
+    """alpha = 1, beta = 0.5, entries uniform[-1,1], seed 1; NN, NT, TN; median of event-timed calls."""
+    out = {}
+    for size in sizes:
+        m = n = k = size
+        A, B, C0 = si.gemm_operands(1, m, k, k, n, m, n, device="cuda:0")
+        for ta, tb in (("N", "N"), ("N", "T"), ("T", "N")):
+            Cm = C0.clone()
+            reps = 30 if size <= 1024 else (10 if size <= 4096 else 5)
+            for _ in range(3):
+                ulsnn.sgemm(ta, tb, m, n, k, 1.0, A, k, B, n, 0.5, Cm, n)
+            torch.cuda.synchronize()
+            times = []
+            for _ in range(reps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                ulsnn.sgemm(ta, tb, m, n, k, 1.0, A, k, B, n, 0.5, Cm, n)
+                e1.record()
+                e1.synchronize()
+                times.append(e0.elapsed_time(e1))
+            times.sort()
+            med = times[len(times) // 2]
+            gf = ulsnn.sgemm_flops(m, n, k) / (med * 1e-3) / 1e9
+            out[f"{ta}{tb}_{size}"] = {"ms": round(med, 4), "gflops": round(gf, 1),
+                                      "frac_of_peak": round(gf / (PEAK_FP32_MFMA_TFLOPS * 1e3), 4)}
+        del A, B, C0
+    return out
+
+
+def cpu_baseline(si, shape, W1, W2, X, y):
+    import numpy as np
+
+    import oracle
+    t0 = time.perf_counter()
+    g = oracle.mlp_grad(W1.numpy(), W2.numpy(), X.numpy(), y.numpy(), dtype=np.float32)
+    dt = time.perf_counter() - t0
+    flops = oracle.grad_flops(X.shape[0], shape.n_in, shape.n_hid, shape.n_out)
+    return {"value": round(flops / dt / 1e9, 3), "unit": "GFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"the whole workload once: {X.shape[0]} patterns, float-arithmetic oracle, {dt:.2f} s",
+            "patterns_per_s": round(X.shape[0] / dt, 1), "loss": g.loss}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU; --gpus {args.gpus} is not supported "
+              f"(the gradient is additive over patterns, so more GPUs would each take a share of the "
+              f"patterns and all-reduce 1,729,441 floats; that path is not built)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_1911_05181_amd as ulsnn
+    import synth_inputs as si
+
+    ulsnn.load()                       # fails loudly if the HIP library has not been built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    shape = si.MLP_JOCR
+    W1c, W2c, _, _ = si.mlp_weights(shape, SEED)
+    Xc, yc = si.mlp_patterns(shape, SEED, 0, BATCH)
+    W1, W2, X, y = W1c.to(dev), W2c.to(dev), Xc.to(dev), yc.to(dev)
+    need = ulsnn.mlp_grad_workspace_bytes(shape.n_in, shape.n_hid, shape.n_out, BATCH)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    out = ulsnn.MlpGradResult(torch.empty_like(W1), torch.empty_like(W2), torch.empty(1, device=dev))
+    flops = ulsnn.mlp_grad_flops(shape.n_in, shape.n_hid, shape.n_out, BATCH)
+
+    for _ in range(args.warmup):
+        ulsnn.mlp_grad(W1, W2, X, y, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ulsnn.mlp_grad(W1, W2, X, y, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    gflops = flops * args.steps / dt / 1e9
+    loss = out.loss.item()
+
+    # per-stage durations from HIP events on the launch stream (same kernels, same workspace)
+    reps = max(5, min(args.steps, 20))
+    acc = {k: 0.0 for k in ulsnn.MLP_STAGES}
+    for _ in range(reps):
+        _, ms = ulsnn.mlp_grad_timed(W1, W2, X, y, out=out, workspace=ws)
+        for k, v in ms.items():
+            acc[k] += v / reps
+    n_i, n_h, n_o = shape.n_in, shape.n_hid, shape.n_out
+    stage_flops = {"hidden_layer": 2.0 * BATCH * n_i * n_h, "output_layer": 2.0 * BATCH * n_h * n_o,
+                   "dW2": 2.0 * BATCH * n_h * n_o, "hidden_delta": 2.0 * BATCH * n_h * n_o,
+                   "dW1": 2.0 * BATCH * n_i * n_h}
+    stages = {k: {"ms": round(v, 4), "tflops": round(stage_flops[k] / (v * 1e-3) / 1e12, 2) if k in stage_flops
+                  and v > 0 else None} for k, v in acc.items()}
+    dom = max(stage_flops, key=lambda k: acc[k])
+    achieved = stage_flops[dom] / (acc[dom] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": f"gemm_kernel ({dom} product)", "achieved": round(achieved, 2),
+                "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4),
+                "traffic": None, "flops_per_launch": stage_flops[dom], "avg_launch_ms": round(acc[dom], 4)}
+
+    result = {
+        "metric": METRIC, "value": round(gflops, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "mlp_grad 400-480-3203 (1,729,440 parameters, no biases), batch 4096, seed 2 "
+                               "(BASELINE configs[2]); sgemm sweep = configs[1]",
+                   "batch": BATCH, "flops_per_step": flops},
+        "patterns_per_s": round(BATCH * args.steps / dt, 1),
+        "frac_of_fp32_mfma_peak": round(gflops / (PEAK_FP32_MFMA_TFLOPS * 1e3), 4),
+        "loss": loss, "stages": stages, "roofline": roofline,
+    }
+    if not args.no_sgemm:
+        result["sgemm"] = bench_sgemm(ulsnn, si, torch, args.sgemm_sizes)
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(si, shape, W1c, W2c, Xc, yc)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -45,11 +45,25 @@ struct GemmArgs {
     int kchunk;          // k range handled per blockIdx.y (multiple of BK); >= K when there is no split
     int tiles_m, tiles_n;
     size_t partial_stride;  // EPI_PARTIAL: elements between consecutive partial results
+#ifdef ULSNN_TRACE
+    long long *trace;       // diagnostic builds only: 6 timestamps/ids per workgroup
+#endif
 };
 
-template <int BM_, int BN_, int BK_, int WM_, int WN_>
+#ifdef ULSNN_TRACE
+#define ULSNN_STAMP(slot)                                                                              \
+    do {                                                                                               \
+        if (g.trace && threadIdx.x == 0)                                                               \
+            g.trace[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 6 + (slot)] = wall_clock64();      \
+    } while (0)
+#else
+#define ULSNN_STAMP(slot) do { } while (0)
+#endif
+
+// WAVES_PER_SIMD_ is the occupancy the register allocation must allow (wavefronts per SIMD).
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int WAVES_PER_SIMD_ = 1>
 struct TileCfg {
-    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, WAVES_PER_SIMD = WAVES_PER_SIMD_;
     static constexpr int THREADS = WM * WN * 64;
     static constexpr int WTM = BM / WM, WTN = BN / WN;   // wavefront sub-tile
     static constexpr int TM = WTM / 32, TN = WTN / 32;   // 32x32 accumulator blocks per wavefront
@@ -182,8 +196,92 @@ __device__ __forceinline__ float tanh_f32(float x)
     return copysignf(r, x);
 }
 
+// Per-thread state of the unchecked fetch used for full k blocks.  The tile's base pointer (uniform) already
+// points at (first row of the tile, first k of the workgroup); `off` is this thread's element offset from it
+// and never changes, the base advances by BK (KC) or BK*ld (MC) per step.  A 16-byte load that lies wholly
+// beyond the matrix edge is redirected to a valid address (row clamped for KC, first column of the tile for
+// MC): its values only reach accumulators that are never stored.  Only an MC load that STRADDLES the edge
+// (possible when the valid width is not a multiple of 4) needs guarded 4-byte loads: bit set in `edge`.
+template <bool KC, int R, int BK, int THREADS, int NV>
+struct FastFetch {
+    unsigned off[NV];
+    unsigned edge;
+    int valid;   // rows/columns of this tile inside the matrix
+
+    __device__ __forceinline__ void init(int ld, int r0, int rmax, int tid)
+    {
+        constexpr int TOTAL = R * BK / 4;
+        edge = 0;
+        valid = rmax - r0;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            int f = tid + v * THREADS;
+            if (TOTAL % THREADS != 0 && f >= TOTAL) f = 0;   // nothing to fetch: repeat a valid load (not stored)
+            if (KC) {
+                int row = f / (BK / 4);
+                const int kq = (f % (BK / 4)) * 4;
+                row = row < valid ? row : valid - 1;
+                off[v] = (unsigned)row * (unsigned)ld + (unsigned)kq;
+            } else {
+                const int krow = f / (R / 4);
+                int rq = (f % (R / 4)) * 4;
+                if (rq >= valid) rq = 0;
+                else if (rq + 3 >= valid) edge |= 1u << v;
+                off[v] = (unsigned)krow * (unsigned)ld + (unsigned)rq;
+            }
+        }
+    }
+
+    __device__ __forceinline__ void fetch(floatx4 (&reg)[NV], const float *__restrict__ base, int tid) const
+    {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const float *src = base + off[v];
+            if (KC || !(edge >> v & 1)) {
+                reg[v] = load4_any_align(src);
+            } else {
+                const int rq = ((tid + v * THREADS) % (R / 4)) * 4;
+                floatx4 val = {0.f, 0.f, 0.f, 0.f};
+                if (rq + 0 < valid) val.x = src[0];
+                if (rq + 1 < valid) val.y = src[1];
+                if (rq + 2 < valid) val.z = src[2];
+                reg[v] = val;
+            }
+        }
+    }
+};
+
+// Operand fragments of one group of four 32x32x2 products for a wavefront's whole sub-tile.
+template <class Cfg>
+struct Fragments {
+    floatx4 a[Cfg::TM], b[Cfg::TN];
+};
+
+template <class Cfg, bool A_KC, bool B_KC>
+__device__ __forceinline__ void read_fragments(Fragments<Cfg> &f, const float *la, const float *lb, int s, int wrow,
+                                               int wcol, int l32, int h)
+{
+#pragma unroll
+    for (int x = 0; x < Cfg::TM; ++x) f.a[x] = panel_read<A_KC, Cfg::BM, Cfg::BK>(la, wrow + x * 32, s, l32, h);
+#pragma unroll
+    for (int y = 0; y < Cfg::TN; ++y) f.b[y] = panel_read<B_KC, Cfg::BN, Cfg::BK>(lb, wcol + y * 32, s, l32, h);
+}
+
+// Products t0 <= t < t1 of a group, for every accumulator block of the wavefront.
+template <class Cfg, int T0, int T1>
+__device__ __forceinline__ void multiply(floatx16 (&acc)[Cfg::TM][Cfg::TN], const Fragments<Cfg> &f)
+{
+#pragma unroll
+    for (int t = T0; t < T1; ++t)
+#pragma unroll
+        for (int x = 0; x < Cfg::TM; ++x)
+#pragma unroll
+            for (int y = 0; y < Cfg::TN; ++y)
+                acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[x][t], f.b[y][t], acc[x][y], 0, 0, 0);
+}
+
 template <class Cfg, bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(const GemmArgs g)
+__global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm_kernel(const GemmArgs g)
 {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, THREADS = Cfg::THREADS;
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
@@ -199,6 +297,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(const GemmArgs g)
     const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
     const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
+    const int wrow = wm * Cfg::WTM, wcol = wn * Cfg::WTN;
 
     int tile_m, tile_n;
     tile_of_workgroup(blockIdx.x, g.tiles_m, g.tiles_n, tile_m, tile_n);
@@ -206,7 +305,19 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(const GemmArgs g)
     const int z = blockIdx.y;
     const int kbeg = z * g.kchunk;
     const int kend = (kbeg + g.kchunk < g.K) ? kbeg + g.kchunk : g.K;
-    const int nkb = (kend - kbeg + BK - 1) / BK;
+    ULSNN_STAMP(0);
+#ifdef ULSNN_TRACE
+    if (g.trace && threadIdx.x == 0) {
+        unsigned hwid, xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        g.trace[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 6 + 4] = hwid;
+        g.trace[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 6 + 5] = xcc;
+    }
+#endif
+    const int nfull = (kend - kbeg) / BK;             // steps fetched without any check
+    const bool tail = (kend - kbeg) % BK != 0;        // one last, partial step: checked fetch, zero filled
+    const int nkb = nfull + (tail ? 1 : 0);
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -216,16 +327,64 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(const GemmArgs g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
+    FastFetch<A_KC, BM, BK, THREADS, NVA> fa;
+    FastFetch<B_KC, BN, BK, THREADS, NVB> fb;
+    fa.init(g.lda, i0, g.M, tid);
+    fb.init(g.ldb, j0, g.N, tid);
+    // uniform base pointers of the tile at k = kbeg, and their advance per step
+    const float *pa = A_KC ? g.A + (size_t)i0 * g.lda + kbeg : g.A + (size_t)kbeg * g.lda + i0;
+    const float *pb = B_KC ? g.B + (size_t)j0 * g.ldb + kbeg : g.B + (size_t)kbeg * g.ldb + j0;
+    const size_t step_a = A_KC ? (size_t)BK : (size_t)BK * g.lda;
+    const size_t step_b = B_KC ? (size_t)BK : (size_t)BK * g.ldb;
+
     floatx4 ra[NVA], rb[NVB];
+#pragma unroll
+    for (int v = 0; v < NVA; ++v) ra[v] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int v = 0; v < NVB; ++v) rb[v] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    constexpr int S = BK / 8;   // groups of four products per step
+
     if (nkb > 0) {
-        panel_fetch<A_KC, BM, BK, THREADS, NVA>(ra, g.A, g.lda, i0, g.M, kbeg, kend, tid);
-        panel_fetch<B_KC, BN, BK, THREADS, NVB>(rb, g.B, g.ldb, j0, g.N, kbeg, kend, tid);
+        if (nfull > 0) {
+            fa.fetch(ra, pa, tid);
+            fb.fetch(rb, pb, tid);
+        } else {
+            panel_fetch<A_KC, BM, BK, THREADS, NVA>(ra, g.A, g.lda, i0, g.M, kbeg, kend, tid);
+            panel_fetch<B_KC, BN, BK, THREADS, NVB>(rb, g.B, g.ldb, j0, g.N, kbeg, kend, tid);
+        }
         panel_store<A_KC, BM, BK, THREADS, NVA>(lds_a[0], ra, tid);
         panel_store<B_KC, BN, BK, THREADS, NVB>(lds_b[0], rb, tid);
     }
     __syncthreads();
+    ULSNN_STAMP(1);
 
-    for (int kb = 0; kb < nkb; ++kb) {
+    // All matrix-core work of one step on LDS stage `cur`.  Several workgroups share a compute unit, so the
+    // latency of these LDS reads is covered by the products of the other workgroups' wavefronts.
+    auto compute = [&](int cur) {
+        const float *la = lds_a[cur], *lb = lds_b[cur];
+        Fragments<Cfg> f[S];
+#pragma unroll
+        for (int sg = 0; sg < S; ++sg) read_fragments<Cfg, A_KC, B_KC>(f[sg], la, lb, sg, wrow, wcol, l32, h);
+#pragma unroll
+        for (int sg = 0; sg < S; ++sg) multiply<Cfg, 0, 4>(acc, f[sg]);
+    };
+
+    // full steps whose successor is also a full step: unchecked fetch
+    int kb = 0;
+    for (; kb + 1 < nfull; ++kb) {
+        const int cur = kb & 1;
+        pa += step_a;
+        pb += step_b;
+        fa.fetch(ra, pa, tid);
+        fb.fetch(rb, pb, tid);
+        compute(cur);
+        panel_store<A_KC, BM, BK, THREADS, NVA>(lds_a[cur ^ 1], ra, tid);
+        panel_store<B_KC, BN, BK, THREADS, NVB>(lds_b[cur ^ 1], rb, tid);
+        __syncthreads();
+    }
+    // the last full step (its successor, if any, is the partial step: checked fetch), then the partial step
+    for (; kb < nkb; ++kb) {
         const int cur = kb & 1;
         const bool more = kb + 1 < nkb;
         if (more) {
@@ -233,22 +392,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(const GemmArgs g)
             panel_fetch<A_KC, BM, BK, THREADS, NVA>(ra, g.A, g.lda, i0, g.M, k0, kend, tid);
             panel_fetch<B_KC, BN, BK, THREADS, NVB>(rb, g.B, g.ldb, j0, g.N, k0, kend, tid);
         }
-        const float *la = lds_a[cur], *lb = lds_b[cur];
-#pragma unroll
-        for (int s = 0; s < BK / 8; ++s) {
-            floatx4 a[TM], b[TN];
-#pragma unroll
-            for (int x = 0; x < TM; ++x) a[x] = panel_read<A_KC, BM, BK>(la, wm * Cfg::WTM + x * 32, s, l32, h);
-#pragma unroll
-            for (int y = 0; y < TN; ++y) b[y] = panel_read<B_KC, BN, BK>(lb, wn * Cfg::WTN + y * 32, s, l32, h);
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int x = 0; x < TM; ++x)
-#pragma unroll
-                    for (int y = 0; y < TN; ++y)
-                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[x][t], b[y][t], acc[x][y], 0, 0, 0);
-        }
+        compute(cur);
         if (more) {
             panel_store<A_KC, BM, BK, THREADS, NVA>(lds_a[cur ^ 1], ra, tid);
             panel_store<B_KC, BN, BK, THREADS, NVB>(lds_b[cur ^ 1], rb, tid);
@@ -256,6 +400,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(const GemmArgs g)
         __syncthreads();
     }
 
+    ULSNN_STAMP(2);
     // Epilogue.  Accumulator register r of a 32x32 block holds row 8*(r/4) + 4*h + r%4, column lane%32.
     float *Cout = g.C;
     int ldc = g.ldc;
@@ -294,6 +439,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_kernel(const GemmArgs g)
             }
         }
     }
+    ULSNN_STAMP(3);
 }
 
 }  // namespace ulsnn
