@@ -134,13 +134,12 @@ def main():
             acc[k] += v / reps
     n_i, n_h, n_o = shape.n_in, shape.n_hid, shape.n_out
     stage_flops = {"hidden_layer": 2.0 * BATCH * n_i * n_h, "output_layer": 2.0 * BATCH * n_h * n_o,
-                   "dW2": 2.0 * BATCH * n_h * n_o, "hidden_delta": 2.0 * BATCH * n_h * n_o,
-                   "dW1": 2.0 * BATCH * n_i * n_h}
+                   "backward_products": 4.0 * BATCH * n_h * n_o, "dW1_product": 2.0 * BATCH * n_i * n_h}
     stages = {k: {"ms": round(v, 4), "tflops": round(stage_flops[k] / (v * 1e-3) / 1e12, 2) if k in stage_flops
                   and v > 0 else None} for k, v in acc.items()}
     dom = max(stage_flops, key=lambda k: acc[k])
     achieved = stage_flops[dom] / (acc[dom] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": f"gemm_kernel ({dom} product)", "achieved": round(achieved, 2),
+    roofline = {"bound": "mfma", "kernel": f"fp32 MFMA GEMM launch of stage '{dom}'", "achieved": round(achieved, 2),
                 "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4),
                 "traffic": None, "flops_per_launch": stage_flops[dom], "avg_launch_ms": round(acc[dom], 4)}
 

@@ -131,9 +131,10 @@ int ulsnn_mlp_grad_epoch(const ulsnn_mlp_desc *desc, const void *W1, const void 
  * Diagnostic form of ulsnn_mlp_grad for measurement: the same work on the same kernels, with a HIP event
  * recorded on the stream at each stage boundary.  The call WAITS for the stream to finish and writes the
  * elapsed milliseconds of the ULSNN_MLP_STAGES stages to the HOST array stage_ms:
- *   0 hidden layer (H)   1 output layer (Z)   2 softmax, cross-entropy, output delta, loss sum
- *   3 dW2 = H^T dO       4 db2                5 hidden delta (dA1)      6 dW1 = X^T dA1      7 db1
- * (section 4.2 names the products; stages 4 and 7 are empty without biases).  Only batches that fit one
+ *   0 hidden layer (H)            1 output layer (Z)        2 softmax, cross-entropy, output delta, loss sum
+ *   3 backward products: hidden delta dA1 = dO W2^T and dW2 = H^T dO (one paired launch when both are k-split)
+ *   4 their split-k reductions    5 dW1 = X^T dA1 product   6 its split-k reduction      7 bias gradients
+ * (section 4.2 names the products; stages 4 and 6 are empty without a k split, 7 without biases).  Only batches that fit one
  * internal pass are accepted (1 <= batch <= 16384), otherwise ULSNN_ERR_UNSUPPORTED.  Creates and destroys
  * HIP events; allocates no device memory.
  */
@@ -141,6 +142,13 @@ int ulsnn_mlp_grad_epoch(const ulsnn_mlp_desc *desc, const void *W1, const void 
 int ulsnn_mlp_grad_timed(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X,
                          const int32_t *labels, int batch, float *dW1, float *dW2, float *loss,
                          float *stage_ms);
+
+/*
+ * Host-only diagnostic: writes to buf (NUL-terminated, truncated to buf_bytes) one line per matrix product of
+ * the gradient (section 4.2) with the tile shape, tile grid, k split and modelled time this build would use
+ * for `batch` patterns (for the first internal pass if the batch is processed in several).  Launches nothing.
+ */
+int ulsnn_mlp_grad_describe_plan(const ulsnn_mlp_desc *desc, int batch, char *buf, size_t buf_bytes);
 
 /* Counting conventions (host-only): 2mnk (section 3.1) and batch*(4 n_in n_hid + 6 n_hid n_out) (section 6.2). */
 double ulsnn_sgemm_flops(int m, int n, int k);

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     lib_path,
     load,
     mlp_grad,
+    mlp_grad_describe_plan,
     mlp_grad_epoch,
     mlp_grad_flops,
     mlp_grad_timed,

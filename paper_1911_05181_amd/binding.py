@@ -55,6 +55,8 @@ def load():
     L.ulsnn_mlp_grad_epoch.restype = i
     L.ulsnn_mlp_grad_timed.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, i, vp, vp, vp, C.POINTER(C.c_float)]
     L.ulsnn_mlp_grad_timed.restype = i
+    L.ulsnn_mlp_grad_describe_plan.argtypes = [C.POINTER(_MlpDesc), i, C.c_char_p, C.c_size_t]
+    L.ulsnn_mlp_grad_describe_plan.restype = i
     L.ulsnn_sgemm_flops.argtypes = [i, i, i]
     L.ulsnn_sgemm_flops.restype = C.c_double
     L.ulsnn_mlp_grad_flops.argtypes = [i, i, i, C.c_int64]
@@ -128,6 +130,17 @@ def mlp_grad_workspace_bytes(n_in: int, n_hid: int, n_out: int, batch: int) -> i
     return int(load().ulsnn_mlp_grad_workspace_bytes(C.byref(d), batch))
 
 
+def mlp_grad_describe_plan(n_in: int, n_hid: int, n_out: int, batch: int) -> str:
+    """Tile shapes, k splits and modelled times the library would use (host-only; launches nothing)."""
+    d = _MlpDesc()
+    d.n_in, d.n_hid, d.n_out = n_in, n_hid, n_out
+    buf = C.create_string_buffer(2048)
+    rc = load().ulsnn_mlp_grad_describe_plan(C.byref(d), batch, buf, len(buf))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_mlp_grad_describe_plan")
+    return buf.value.decode()
+
+
 @dataclass
 class MlpGradResult:
     dW1: torch.Tensor
@@ -176,7 +189,8 @@ def mlp_grad(W1, W2, X, labels, b1=None, b2=None, *, out: Optional[MlpGradResult
     return out
 
 
-MLP_STAGES = ("hidden_layer", "output_layer", "softmax_ce", "dW2", "db2", "hidden_delta", "dW1", "db1")
+MLP_STAGES = ("hidden_layer", "output_layer", "softmax_ce", "backward_products", "backward_reductions",
+              "dW1_product", "dW1_reduction", "bias_grads")
 
 
 def mlp_grad_timed(W1, W2, X, labels, b1=None, b2=None, *, out: Optional[MlpGradResult] = None, accumulate=False,

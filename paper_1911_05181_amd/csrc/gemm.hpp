@@ -46,15 +46,14 @@ struct GemmArgs {
     int tiles_m, tiles_n;
     size_t partial_stride;  // EPI_PARTIAL: elements between consecutive partial results
 #ifdef ULSNN_TRACE
-    long long *trace;       // diagnostic builds only: 6 timestamps/ids per workgroup
+    long long *trace;       // diagnostic builds only: 8 timestamps/ids per workgroup
 #endif
 };
 
 #ifdef ULSNN_TRACE
 #define ULSNN_STAMP(slot)                                                                              \
     do {                                                                                               \
-        if (g.trace && threadIdx.x == 0)                                                               \
-            g.trace[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 6 + (slot)] = wall_clock64();      \
+        if (g.trace && threadIdx.x == 0) g.trace[(size_t)wg_linear * 8 + (slot)] = wall_clock64();     \
     } while (0)
 #else
 #define ULSNN_STAMP(slot) do { } while (0)
@@ -280,8 +279,18 @@ __device__ __forceinline__ void multiply(floatx16 (&acc)[Cfg::TM][Cfg::TN], cons
                 acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[x][t], f.b[y][t], acc[x][y], 0, 0, 0);
 }
 
+// LDS floats one workgroup needs: two stages of an A panel and a B panel.
+template <class Cfg, bool A_KC, bool B_KC>
+constexpr int gemm_lds_floats()
+{
+    return 2 * (Panel<A_KC, Cfg::BM, Cfg::BK>::SIZE + Panel<B_KC, Cfg::BN, Cfg::BK>::SIZE);
+}
+
+// The work of one workgroup: tile number `pid` (before the XCD / group remapping) of k split `z`.
+// `lds` points at gemm_lds_floats() floats of 16-byte aligned LDS.
 template <class Cfg, bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm_kernel(const GemmArgs g)
+__device__ __forceinline__ void gemm_tile(const GemmArgs &g, const int pid, const int z, float *lds,
+                                          const int wg_linear)
 {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, THREADS = Cfg::THREADS;
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
@@ -289,9 +298,10 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm_kernel
     using PB = Panel<B_KC, BN, BK>;
     constexpr int NVA = (BM * BK / 4 + THREADS - 1) / THREADS;
     constexpr int NVB = (BN * BK / 4 + THREADS - 1) / THREADS;
+    (void)wg_linear;
 
-    __shared__ __attribute__((aligned(16))) float lds_a[2][PA::SIZE];
-    __shared__ __attribute__((aligned(16))) float lds_b[2][PB::SIZE];
+    auto stage_a = [&](int st) { return lds + st * PA::SIZE; };
+    auto stage_b = [&](int st) { return lds + 2 * PA::SIZE + st * PB::SIZE; };
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -300,9 +310,8 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm_kernel
     const int wrow = wm * Cfg::WTM, wcol = wn * Cfg::WTN;
 
     int tile_m, tile_n;
-    tile_of_workgroup(blockIdx.x, g.tiles_m, g.tiles_n, tile_m, tile_n);
+    tile_of_workgroup(pid, g.tiles_m, g.tiles_n, tile_m, tile_n);
     const int i0 = tile_m * BM, j0 = tile_n * BN;
-    const int z = blockIdx.y;
     const int kbeg = z * g.kchunk;
     const int kend = (kbeg + g.kchunk < g.K) ? kbeg + g.kchunk : g.K;
     ULSNN_STAMP(0);
@@ -311,8 +320,9 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm_kernel
         unsigned hwid, xcc;
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-        g.trace[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 6 + 4] = hwid;
-        g.trace[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 6 + 5] = xcc;
+        g.trace[(size_t)wg_linear * 8 + 4] = hwid;
+        g.trace[(size_t)wg_linear * 8 + 5] = xcc;
+        g.trace[(size_t)wg_linear * 8 + 6] = clock64();
     }
 #endif
     const int nfull = (kend - kbeg) / BK;             // steps fetched without any check
@@ -353,8 +363,8 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm_kernel
             panel_fetch<A_KC, BM, BK, THREADS, NVA>(ra, g.A, g.lda, i0, g.M, kbeg, kend, tid);
             panel_fetch<B_KC, BN, BK, THREADS, NVB>(rb, g.B, g.ldb, j0, g.N, kbeg, kend, tid);
         }
-        panel_store<A_KC, BM, BK, THREADS, NVA>(lds_a[0], ra, tid);
-        panel_store<B_KC, BN, BK, THREADS, NVB>(lds_b[0], rb, tid);
+        panel_store<A_KC, BM, BK, THREADS, NVA>(stage_a(0), ra, tid);
+        panel_store<B_KC, BN, BK, THREADS, NVB>(stage_b(0), rb, tid);
     }
     __syncthreads();
     ULSNN_STAMP(1);
@@ -362,7 +372,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm_kernel
     // All matrix-core work of one step on LDS stage `cur`.  Several workgroups share a compute unit, so the
     // latency of these LDS reads is covered by the products of the other workgroups' wavefronts.
     auto compute = [&](int cur) {
-        const float *la = lds_a[cur], *lb = lds_b[cur];
+        const float *la = stage_a(cur), *lb = stage_b(cur);
         Fragments<Cfg> f[S];
 #pragma unroll
         for (int sg = 0; sg < S; ++sg) read_fragments<Cfg, A_KC, B_KC>(f[sg], la, lb, sg, wrow, wcol, l32, h);
@@ -379,8 +389,8 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm_kernel
         fa.fetch(ra, pa, tid);
         fb.fetch(rb, pb, tid);
         compute(cur);
-        panel_store<A_KC, BM, BK, THREADS, NVA>(lds_a[cur ^ 1], ra, tid);
-        panel_store<B_KC, BN, BK, THREADS, NVB>(lds_b[cur ^ 1], rb, tid);
+        panel_store<A_KC, BM, BK, THREADS, NVA>(stage_a(cur ^ 1), ra, tid);
+        panel_store<B_KC, BN, BK, THREADS, NVB>(stage_b(cur ^ 1), rb, tid);
         __syncthreads();
     }
     // the last full step (its successor, if any, is the partial step: checked fetch), then the partial step
@@ -394,8 +404,8 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm_kernel
         }
         compute(cur);
         if (more) {
-            panel_store<A_KC, BM, BK, THREADS, NVA>(lds_a[cur ^ 1], ra, tid);
-            panel_store<B_KC, BN, BK, THREADS, NVB>(lds_b[cur ^ 1], rb, tid);
+            panel_store<A_KC, BM, BK, THREADS, NVA>(stage_a(cur ^ 1), ra, tid);
+            panel_store<B_KC, BN, BK, THREADS, NVB>(stage_b(cur ^ 1), rb, tid);
         }
         __syncthreads();
     }
@@ -440,6 +450,38 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm_kernel
         }
     }
     ULSNN_STAMP(3);
+#ifdef ULSNN_TRACE
+    if (g.trace && threadIdx.x == 0) g.trace[(size_t)wg_linear * 8 + 7] = clock64();
+#endif
+}
+
+// One GEMM per launch: grid = (tiles, k splits).
+template <class Cfg, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm_kernel(const GemmArgs g)
+{
+    __shared__ __attribute__((aligned(16))) float lds[gemm_lds_floats<Cfg, A_KC, B_KC>()];
+    gemm_tile<Cfg, A_KC, B_KC, EPI>(g, blockIdx.x, blockIdx.y, lds, blockIdx.y * gridDim.x + blockIdx.x);
+}
+
+// Two independent GEMMs in one launch (1-D grid): workgroups [0, n1) work on g1, the rest on g2.  The second
+// problem's workgroups start as the first one's finish, so the compute units stay full across the seam and
+// one problem's stores overlap the other's products.  Both tile shapes must use the same number of threads.
+template <class Cfg1, bool A_KC1, bool B_KC1, int EPI1, class Cfg2, bool A_KC2, bool B_KC2, int EPI2>
+__global__ __launch_bounds__(Cfg1::THREADS, (Cfg1::WAVES_PER_SIMD < Cfg2::WAVES_PER_SIMD ? Cfg1::WAVES_PER_SIMD
+                                                                                         : Cfg2::WAVES_PER_SIMD))
+void gemm_pair_kernel(const GemmArgs g1, const GemmArgs g2, const int n1)
+{
+    static_assert(Cfg1::THREADS == Cfg2::THREADS, "paired tile shapes need equal workgroup sizes");
+    constexpr int L1 = gemm_lds_floats<Cfg1, A_KC1, B_KC1>(), L2 = gemm_lds_floats<Cfg2, A_KC2, B_KC2>();
+    __shared__ __attribute__((aligned(16))) float lds[L1 > L2 ? L1 : L2];
+    const int id = blockIdx.x;
+    if (id < n1) {
+        const int t = g1.tiles_m * g1.tiles_n;
+        gemm_tile<Cfg1, A_KC1, B_KC1, EPI1>(g1, id % t, id / t, lds, id);
+    } else {
+        const int t = g2.tiles_m * g2.tiles_n, r = id - n1;
+        gemm_tile<Cfg2, A_KC2, B_KC2, EPI2>(g2, r % t, r / t, lds, id);
+    }
 }
 
 }  // namespace ulsnn

@@ -5,7 +5,9 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdint>
+#include <cstdio>
 
 #include "gemm.hpp"
 #include "mlp_kernels.hpp"
@@ -22,52 +24,118 @@ inline bool is_t(char t) { return t == 'T' || t == 't' || t == 'C' || t == 'c'; 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---------------------------------------------------------------------------------------------------------
-// GEMM dispatch
+// GEMM dispatch: tile shapes, the cost model that picks one (and a k split), and the launchers
 // ---------------------------------------------------------------------------------------------------------
 
-using Cfg128 = TileCfg<128, 128, 16, 2, 2>;   // 256 threads, wavefront tile 64 x 64
-using Cfg64 = TileCfg<64, 64, 16, 2, 2>;      // 256 threads, wavefront tile 32 x 32 (small problems)
+// Tile shapes.  The last template argument is the number of wavefronts per SIMD the register allocation must
+// allow, chosen so that LDS and registers admit the same number of workgroups per compute unit.
+using Cfg256x128 = TileCfg<256, 128, 16, 4, 2, 4>;   // 512 threads, 2 workgroups / CU: large problems
+using Cfg128w8 = TileCfg<128, 128, 16, 4, 2, 6>;     // 512 threads, 3 workgroups / CU
+using Cfg128 = TileCfg<128, 128, 16, 2, 2, 4>;       // 256 threads, 4 workgroups / CU
+using Cfg128x64 = TileCfg<128, 64, 16, 2, 2, 5>;     // 256 threads, 5 workgroups / CU
+using Cfg64x128 = TileCfg<64, 128, 16, 2, 2, 5>;     // 256 threads, 5 workgroups / CU
+using Cfg64 = TileCfg<64, 64, 16, 2, 2, 8>;          // 256 threads, 8 workgroups / CU: small problems
 
-enum CfgId { CFG_128 = 0, CFG_64 = 1 };
+enum CfgId { CFG_256x128 = 0, CFG_128W8, CFG_128, CFG_128x64, CFG_64x128, CFG_64, CFG_COUNT };
+
+struct CfgInfo {
+    int bm, bn, bk, threads, occ;   // occ = resident workgroups per compute unit
+    double eff;                     // matrix-core efficiency of the steady state relative to the best shape
+    const char *name;
+};
+
+constexpr CfgInfo CFG_INFO[CFG_COUNT] = {
+    {256, 128, 16, 512, 2, 1.00, "256x128"}, {128, 128, 16, 512, 3, 0.98, "128x128w8"},
+    {128, 128, 16, 256, 4, 0.97, "128x128"}, {128, 64, 16, 256, 5, 0.93, "128x64"},
+    {64, 128, 16, 256, 5, 0.93, "64x128"},   {64, 64, 16, 256, 8, 0.86, "64x64"},
+};
 
 struct GemmPlan {
     CfgId cfg;
-    int bm, bn, bk;
     int tiles_m, tiles_n;
     int splits, kchunk;
+    double est_us;
 };
 
-inline void cfg_dims(CfgId c, int &bm, int &bn, int &bk)
+// Fraction of the matrix-core rate a SIMD reaches with w resident wavefronts (measured: one wavefront cannot
+// hide its own LDS, barrier and global-load latency; four can).
+inline double simd_utilisation(double w)
 {
-    switch (c) {
-        case CFG_128: bm = Cfg128::BM; bn = Cfg128::BN; bk = Cfg128::BK; break;
-        default: bm = Cfg64::BM; bn = Cfg64::BN; bk = Cfg64::BK; break;
-    }
+    static const double u[5] = {0.0, 0.60, 0.78, 0.86, 0.90};
+    if (w >= 4.0) return u[4];
+    if (w <= 1.0) return u[1];
+    const int lo = (int)w;
+    return u[lo] + (u[lo + 1] - u[lo]) * (w - lo);
 }
 
-// Choose a tile shape and, if allowed, a k split so that the launch has enough workgroups for 256 CUs.
-GemmPlan plan_gemm(int m, int n, int k, bool allow_split)
+// Estimated run time of one launch (+ the split-k reduction), in microseconds.  Not a simulator: a consistent
+// way to trade tile efficiency against how evenly the workgroups fill 256 compute units.
+double model_us(const CfgInfo &c, bool a_kc, bool b_kc, int m, int n, int k, int splits, int *kchunk_out,
+                int *splits_out)
 {
-    GemmPlan p;
-    const long t128 = (long)((m + 127) / 128) * ((n + 127) / 128);
-    p.cfg = (t128 >= NUM_CU || allow_split) ? CFG_128 : CFG_64;
-    cfg_dims(p.cfg, p.bm, p.bn, p.bk);
-    p.tiles_m = (m + p.bm - 1) / p.bm;
-    p.tiles_n = (n + p.bn - 1) / p.bn;
-    p.splits = 1;
-    p.kchunk = std::max(k, 1);
-    const long tiles = (long)p.tiles_m * p.tiles_n;
-    if (allow_split && tiles < 2 * NUM_CU) {
-        int want = (int)((2 * NUM_CU + tiles - 1) / tiles);
-        const int max_by_k = std::max(1, k / (8 * p.bk));         // keep at least 8 k steps per split
-        want = std::min(want, max_by_k);
-        if (want > 1) {
-            const int chunk = (int)round_up((size_t)(k + want - 1) / want, p.bk);
-            p.kchunk = chunk;
-            p.splits = (k + chunk - 1) / chunk;
+    const int chunk = (int)round_up((size_t)(k + splits - 1) / splits, c.bk);
+    const int sp = (k + chunk - 1) / chunk;
+    *kchunk_out = chunk;
+    *splits_out = sp;
+    const long tiles = (long)((m + c.bm - 1) / c.bm) * ((n + c.bn - 1) / c.bn);
+    const long wgs = tiles * sp;
+    const double layout = (!a_kc && !b_kc) ? 0.92 : (a_kc && b_kc) ? 1.0 : 0.97;   // 4-byte LDS reads cost more
+    const double cu_rate = 155.0e12 / NUM_CU * c.eff * layout;                     // flop/s of one compute unit
+    const double flops_wg = 2.0 * c.bm * c.bn * (double)chunk;
+    const double wps = c.threads / 256.0;                                          // wavefronts per SIMD per WG
+    const long slots = (long)NUM_CU * c.occ;
+    const long full = wgs / slots, rem = wgs % slots;
+    double t = full * c.occ * flops_wg / (cu_rate * simd_utilisation(c.occ * wps));
+    if (rem) {
+        const double per_cu = std::ceil((double)rem / NUM_CU);
+        t += per_cu * flops_wg / (cu_rate * simd_utilisation(per_cu * wps));
+    }
+    t += 3.0e-6 + (double)m * n * sp * 4.0 / 4.0e12;                               // ramp-up and the store burst
+    if (sp > 1) t += 3.0e-6 + (double)m * n * (sp + 1.0) * 4.0 / 5.0e12;            // reduction pass
+    return t * 1e6;
+}
+
+// Choose tile shape and k split.  `cfg_mask` restricts the shapes (bit i = CfgId i).
+GemmPlan plan_gemm(int m, int n, int k, bool a_kc, bool b_kc, bool allow_split, unsigned cfg_mask)
+{
+    GemmPlan best{};
+    best.est_us = 1e30;
+    for (int ci = 0; ci < CFG_COUNT; ++ci) {
+        if (!(cfg_mask >> ci & 1)) continue;
+        const CfgInfo &c = CFG_INFO[ci];
+        const int max_splits = allow_split ? std::max(1, std::min(64, k / (8 * c.bk))) : 1;
+        for (int s = 1; s <= max_splits; ++s) {
+            int chunk, sp;
+            const double us = model_us(c, a_kc, b_kc, m, n, std::max(k, 1), s, &chunk, &sp);
+            if (sp != s) continue;   // this s collapses onto a smaller split count already seen
+            if (us < best.est_us) {
+                best.cfg = (CfgId)ci;
+                best.tiles_m = (m + c.bm - 1) / c.bm;
+                best.tiles_n = (n + c.bn - 1) / c.bn;
+                best.splits = sp;
+                best.kchunk = chunk;
+                best.est_us = us;
+            }
         }
     }
-    return p;
+    return best;
+}
+
+constexpr unsigned ALL_CFGS = (1u << CFG_COUNT) - 1;
+constexpr unsigned CFGS_256_THREADS = (1u << CFG_128) | (1u << CFG_128x64) | (1u << CFG_64x128) | (1u << CFG_64);
+constexpr unsigned CFGS_PAIRABLE = (1u << CFG_128) | (1u << CFG_128x64) | (1u << CFG_64x128);
+
+template <class F>
+hipError_t with_cfg(CfgId id, F &&f)
+{
+    switch (id) {
+        case CFG_256x128: return f(Cfg256x128{});
+        case CFG_128W8: return f(Cfg128w8{});
+        case CFG_128: return f(Cfg128{});
+        case CFG_128x64: return f(Cfg128x64{});
+        case CFG_64x128: return f(Cfg64x128{});
+        default: return f(Cfg64{});
+    }
 }
 
 template <class Cfg, bool A_KC, bool B_KC, int EPI>
@@ -87,26 +155,58 @@ hipError_t launch_layout(bool a_kc, bool b_kc, const GemmArgs &a, int splits, hi
     return launch_one<Cfg, false, true, EPI>(a, splits, s);                        // TT
 }
 
-template <class Cfg>
-hipError_t launch_cfg(bool a_kc, bool b_kc, int epi, const GemmArgs &a, int splits, hipStream_t s)
-{
-    switch (epi) {
-        case EPI_AXPBY: return launch_layout<Cfg, EPI_AXPBY>(a_kc, b_kc, a, splits, s);
-        case EPI_PARTIAL: return launch_layout<Cfg, EPI_PARTIAL>(a_kc, b_kc, a, splits, s);
-        case EPI_BIAS_TANH: return launch_one<Cfg, true, false, EPI_BIAS_TANH>(a, splits, s);   // NN only
-        case EPI_BIAS: return launch_one<Cfg, true, false, EPI_BIAS>(a, splits, s);             // NN only
-        default: return launch_one<Cfg, true, true, EPI_TANHGRAD>(a, splits, s);                // NT only
-    }
-}
-
+// Which (shape, layout, epilogue) combinations exist is decided here; the planner's masks match it.
 hipError_t launch_gemm(const GemmPlan &p, bool a_kc, bool b_kc, int epi, GemmArgs a, hipStream_t s)
 {
     a.tiles_m = p.tiles_m;
     a.tiles_n = p.tiles_n;
     a.kchunk = p.kchunk;
-    switch (p.cfg) {
-        case CFG_128: return launch_cfg<Cfg128>(a_kc, b_kc, epi, a, p.splits, s);
-        default: return launch_cfg<Cfg64>(a_kc, b_kc, epi, a, p.splits, s);
+    const int splits = p.splits;
+    return with_cfg(p.cfg, [&](auto cfg) -> hipError_t {
+        using Cfg = decltype(cfg);
+        constexpr bool small = Cfg::THREADS == 256;
+        switch (epi) {
+            case EPI_AXPBY: return launch_layout<Cfg, EPI_AXPBY>(a_kc, b_kc, a, splits, s);
+            case EPI_PARTIAL:
+                if constexpr (small) {
+                    if (a_kc && b_kc) return launch_one<Cfg, true, true, EPI_PARTIAL>(a, splits, s);      // NT
+                    if (!a_kc && !b_kc) return launch_one<Cfg, false, false, EPI_PARTIAL>(a, splits, s);  // TN
+                }
+                return hipErrorInvalidValue;
+            case EPI_BIAS_TANH: return launch_one<Cfg, true, false, EPI_BIAS_TANH>(a, splits, s);   // NN only
+            case EPI_BIAS: return launch_one<Cfg, true, false, EPI_BIAS>(a, splits, s);             // NN only
+            default: return launch_one<Cfg, true, true, EPI_TANHGRAD>(a, splits, s);                // NT only
+        }
+    });
+}
+
+// Hidden-delta product (NT, plan p4) and output-weight-gradient product (TN, plan p3) as ONE launch of split-k
+// partial products: the longer-running workgroups (p4's) are numbered first.
+hipError_t launch_pair_partial(const GemmPlan &p4, GemmArgs a4, const GemmPlan &p3, GemmArgs a3, hipStream_t s)
+{
+    a4.tiles_m = p4.tiles_m; a4.tiles_n = p4.tiles_n; a4.kchunk = p4.kchunk;
+    a3.tiles_m = p3.tiles_m; a3.tiles_n = p3.tiles_n; a3.kchunk = p3.kchunk;
+    const int n4 = p4.tiles_m * p4.tiles_n * p4.splits, n3 = p3.tiles_m * p3.tiles_n * p3.splits;
+    auto second = [&](auto c4) -> hipError_t {
+        using C4 = decltype(c4);
+        auto go = [&](auto c3) -> hipError_t {
+            using C3 = decltype(c3);
+            hipLaunchKernelGGL((gemm_pair_kernel<C4, true, true, EPI_PARTIAL, C3, false, false, EPI_PARTIAL>),
+                               dim3((unsigned)(n4 + n3)), dim3(256), 0, s, a4, a3, n4);
+            return hipGetLastError();
+        };
+        switch (p3.cfg) {
+            case CFG_128: return go(Cfg128{});
+            case CFG_128x64: return go(Cfg128x64{});
+            case CFG_64x128: return go(Cfg64x128{});
+            default: return hipErrorInvalidValue;
+        }
+    };
+    switch (p4.cfg) {
+        case CFG_128: return second(Cfg128{});
+        case CFG_128x64: return second(Cfg128x64{});
+        case CFG_64x128: return second(Cfg64x128{});
+        default: return hipErrorInvalidValue;
     }
 }
 
@@ -115,25 +215,16 @@ inline unsigned grid_for(size_t elems)
     return (unsigned)std::min<size_t>((elems + 255) / 256, (size_t)NUM_CU * 8);
 }
 
-// One product of the MLP gradient: out = epilogue(op(A) op(B)), through a k split when the plan has one.
-// epi is the single-launch epilogue; with a split the same effect is applied by the reduction.
-hipError_t mlp_product(const GemmPlan &p, bool a_kc, bool b_kc, int epi, GemmArgs a, float *partial,
-                       hipStream_t s)
+// The reduction that follows a split-k launch: out = epilogue(sum of partials).
+hipError_t launch_reduce(int splits, int epi, const GemmArgs &a, const float *partial, hipStream_t s)
 {
-    if (p.splits == 1) return launch_gemm(p, a_kc, b_kc, epi, a, s);
-    GemmArgs pa = a;
-    pa.C = partial;
-    pa.partial_stride = (size_t)a.M * a.N;
-    hipError_t e = launch_gemm(p, a_kc, b_kc, EPI_PARTIAL, pa, s);
-    if (e != hipSuccess) return e;
     const size_t total = (size_t)a.M * a.N;
     if (epi == EPI_TANHGRAD) {
-        hipLaunchKernelGGL(splitk_reduce_kernel<true>, dim3(grid_for(total)), dim3(256), 0, s, partial,
-                           pa.partial_stride, p.splits, a.C, a.M, a.N, a.ldc, 1.0f, 0.0f, a.aux, a.ldaux);
+        hipLaunchKernelGGL(splitk_reduce_kernel<true>, dim3(grid_for(total)), dim3(256), 0, s, partial, total, splits,
+                           a.C, a.M, a.N, a.ldc, 1.0f, 0.0f, a.aux, a.ldaux);
     } else {
-        hipLaunchKernelGGL(splitk_reduce_kernel<false>, dim3(grid_for(total)), dim3(256), 0, s, partial,
-                           pa.partial_stride, p.splits, a.C, a.M, a.N, a.ldc, a.alpha, a.beta,
-                           (const float *)nullptr, 0);
+        hipLaunchKernelGGL(splitk_reduce_kernel<false>, dim3(grid_for(total)), dim3(256), 0, s, partial, total,
+                           splits, a.C, a.M, a.N, a.ldc, a.alpha, a.beta, (const float *)nullptr, 0);
     }
     return hipGetLastError();
 }
@@ -142,72 +233,67 @@ hipError_t mlp_product(const GemmPlan &p, bool a_kc, bool b_kc, int epi, GemmArg
 // MLP gradient: plans and workspace layout for one slab of patterns
 // ---------------------------------------------------------------------------------------------------------
 
+constexpr size_t PARTIAL_CAP_FLOATS = (size_t)16 << 20;   // at most 64 MiB of split-k partials per product
+
 struct MlpLayout {
     int slab;                       // rows per pass
     int ldh, ldz;                   // row strides of H / dA1 and of Z / dO
-    size_t off_h, off_z, off_da1, off_rowloss, off_partial, bytes;
+    size_t floats_pa, floats_pb;    // split-k partial regions: A (dW2, then dW1) and B (hidden delta)
+    size_t off_h, off_z, off_da1, off_rowloss, off_pa, off_pb, bytes;
 };
 
 struct SlabPlans {
     GemmPlan g1, g2, g3, g4, g5;
-    size_t partial_floats;
+    bool paired;                    // g4 and g3 run as one launch of partial products
 };
-
-SlabPlans plan_slab(int n_in, int n_hid, int n_out, int rows)
-{
-    SlabPlans s;
-    s.g1 = plan_gemm(rows, n_hid, n_in, false);
-    s.g2 = plan_gemm(rows, n_out, n_hid, false);
-    s.g3 = plan_gemm(n_hid, n_out, rows, true);
-    s.g4 = plan_gemm(rows, n_hid, n_out, true);
-    s.g5 = plan_gemm(n_in, n_hid, rows, true);
-    size_t p = 0;
-    if (s.g3.splits > 1) p = std::max(p, (size_t)s.g3.splits * n_hid * n_out);
-    if (s.g4.splits > 1) p = std::max(p, (size_t)s.g4.splits * rows * n_hid);
-    if (s.g5.splits > 1) p = std::max(p, (size_t)s.g5.splits * n_in * n_hid);
-    s.partial_floats = p;
-    return s;
-}
 
 bool desc_ok(const ulsnn_mlp_desc *d)
 {
     return d && d->n_in >= 1 && d->n_hid >= 1 && d->n_out >= 1;
 }
 
-// Upper bound on the split-k partial floats any pass of at most `slab` rows can need (non-decreasing in slab,
-// so a workspace sized for a batch also serves every smaller one).
-size_t partial_bound(int n_in, int n_hid, int n_out, int slab)
-{
-    int bm, bn, bk;
-    cfg_dims(CFG_128, bm, bn, bk);
-    const long by_k = std::max(1, slab / (8 * bk));
-    auto want = [&](long tiles) { return std::min<long>((2 * NUM_CU + tiles - 1) / tiles, by_k); };
-    const long t3 = (long)((n_hid + bm - 1) / bm) * ((n_out + bn - 1) / bn);
-    const long t5 = (long)((n_in + bm - 1) / bm) * ((n_hid + bn - 1) / bn);
-    size_t p = 0;
-    if (want(t3) > 1) p = std::max(p, (size_t)want(t3) * n_hid * n_out);
-    if (want(t5) > 1) p = std::max(p, (size_t)want(t5) * n_in * n_hid);
-    // hidden delta: splits * rows <= 2*NUM_CU*bm / tiles_n + rows
-    const long tn4 = (n_hid + bn - 1) / bn;
-    p = std::max(p, (size_t)(2 * NUM_CU * bm / tn4 + slab + bm) * n_hid);
-    return p;
-}
-
+// Sizes depend on the network and on min(batch, SLAB_ROWS) only, and do not decrease with the batch, so a
+// workspace sized for a batch also serves every smaller one.
 MlpLayout mlp_layout(const ulsnn_mlp_desc *d, int batch)
 {
     MlpLayout L;
     L.slab = std::max(1, std::min(batch, SLAB_ROWS));
     L.ldh = (int)round_up((size_t)d->n_hid, 32);
     L.ldz = (int)round_up((size_t)d->n_out, 32);
-    const size_t partial = partial_bound(d->n_in, d->n_hid, d->n_out, L.slab);
+    const size_t mn3 = (size_t)d->n_hid * d->n_out, mn5 = (size_t)d->n_in * d->n_hid;
+    const size_t mn4 = (size_t)L.slab * d->n_hid;
+    L.floats_pa = std::max(std::max(mn3, mn5), std::min(PARTIAL_CAP_FLOATS, 64 * std::max(mn3, mn5)));
+    L.floats_pb = std::max(mn4, std::min(PARTIAL_CAP_FLOATS, 16 * mn4));
     size_t off = 0;
     L.off_h = off;        off += round_up((size_t)L.slab * L.ldh * 4, 256);
     L.off_z = off;        off += round_up((size_t)L.slab * L.ldz * 4, 256);
     L.off_da1 = off;      off += round_up((size_t)L.slab * L.ldh * 4, 256);
     L.off_rowloss = off;  off += round_up((size_t)L.slab * 4, 256);
-    L.off_partial = off;  off += round_up(partial * 4, 256);
+    L.off_pa = off;       off += round_up(L.floats_pa * 4, 256);
+    L.off_pb = off;       off += round_up(L.floats_pb * 4, 256);
     L.bytes = off;
     return L;
+}
+
+// Plans of the five products for `rows` patterns.  A split count is limited by the partial region it writes.
+SlabPlans plan_slab(const MlpLayout &L, int n_in, int n_hid, int n_out, int rows)
+{
+    SlabPlans s;
+    auto limited = [](GemmPlan p, int m, int n, int k, bool a_kc, bool b_kc, unsigned mask, size_t region) {
+        // the model may want more splits than the region holds: re-plan without a split in that (rare) case
+        if ((size_t)p.splits * m * n > region) p = plan_gemm(m, n, k, a_kc, b_kc, false, mask);
+        return p;
+    };
+    s.g1 = plan_gemm(rows, n_hid, n_in, true, false, false, ALL_CFGS);
+    s.g2 = plan_gemm(rows, n_out, n_hid, true, false, false, ALL_CFGS);
+    s.g3 = limited(plan_gemm(n_hid, n_out, rows, false, false, true, CFGS_256_THREADS), n_hid, n_out, rows, false,
+                   false, CFGS_256_THREADS, L.floats_pa);
+    s.g4 = limited(plan_gemm(rows, n_hid, n_out, true, true, true, CFGS_256_THREADS), rows, n_hid, n_out, true, true,
+                   CFGS_256_THREADS, L.floats_pb);
+    s.g5 = limited(plan_gemm(n_in, n_hid, rows, false, false, true, CFGS_256_THREADS), n_in, n_hid, rows, false,
+                   false, CFGS_256_THREADS, L.floats_pa);
+    s.paired = s.g3.splits > 1 && s.g4.splits > 1 && (CFGS_PAIRABLE >> s.g3.cfg & 1) && (CFGS_PAIRABLE >> s.g4.cfg & 1);
+    return s;
 }
 
 int check_mlp_args(const ulsnn_mlp_desc *d, const void *W1, const void *W2, const void *X, const int32_t *labels,
@@ -266,12 +352,12 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const float *W1, const float *W2, con
     float *Z = (float *)(ws + L.off_z);
     float *dA1 = (float *)(ws + L.off_da1);
     float *row_loss = (float *)(ws + L.off_rowloss);
-    float *partial = (float *)(ws + L.off_partial);
+    float *part_a = (float *)(ws + L.off_pa);
+    float *part_b = (float *)(ws + L.off_pb);
 
     for (int r0 = 0; r0 < batch; r0 += L.slab) {
         const int rows = std::min(L.slab, batch - r0);
-        const SlabPlans P = plan_slab(n_in, n_hid, n_out, rows);
-        if (L.off_partial + P.partial_floats * 4 > L.bytes) return ULSNN_ERR_WORKSPACE;   // cannot happen
+        const SlabPlans P = plan_slab(L, n_in, n_hid, n_out, rows);
         const float beta = (r0 > 0 || accumulate) ? 1.0f : 0.0f;
         const float *Xs = X + (size_t)r0 * n_in;
         const int32_t *ys = labels + r0;
@@ -304,34 +390,52 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const float *W1, const float *W2, con
         HIP_TRY(hipGetLastError());
         MARK(3);
 
-        // dW2 (+)= H^T dO
-        a = GemmArgs{};
-        a.A = H; a.lda = L.ldh; a.B = Z; a.ldb = L.ldz; a.C = dW2; a.ldc = n_out;
-        a.M = n_hid; a.N = n_out; a.K = rows; a.alpha = 1.f; a.beta = beta;
-        HIP_TRY(mlp_product(P.g3, false, false, EPI_AXPBY, a, partial, s));
-        MARK(4);
-        if (biases) {
-            hipLaunchKernelGGL(column_sum_kernel, dim3((n_out + 63) / 64), dim3(256), 0, s, Z, L.ldz, rows, n_out,
-                               d->db2, beta);
-            HIP_TRY(hipGetLastError());
+        // dW2 (+)= H^T dO   and   dA1 = (dO W2^T) * (1 - H*H): independent of each other
+        GemmArgs a3{}, a4{};
+        a3.A = H; a3.lda = L.ldh; a3.B = Z; a3.ldb = L.ldz; a3.C = dW2; a3.ldc = n_out;
+        a3.M = n_hid; a3.N = n_out; a3.K = rows; a3.alpha = 1.f; a3.beta = beta;
+        a4.A = Z; a4.lda = L.ldz; a4.B = W2; a4.ldb = n_out; a4.C = dA1; a4.ldc = L.ldh;
+        a4.M = rows; a4.N = n_hid; a4.K = n_out; a4.alpha = 1.f; a4.beta = 0.f; a4.aux = H; a4.ldaux = L.ldh;
+        if (P.paired) {
+            GemmArgs p3 = a3, p4 = a4;
+            p3.C = part_a; p3.partial_stride = (size_t)a3.M * a3.N;
+            p4.C = part_b; p4.partial_stride = (size_t)a4.M * a4.N;
+            HIP_TRY(launch_pair_partial(P.g4, p4, P.g3, p3, s));
+            MARK(4);
+            HIP_TRY(launch_reduce(P.g4.splits, EPI_TANHGRAD, a4, part_b, s));
+            HIP_TRY(launch_reduce(P.g3.splits, EPI_AXPBY, a3, part_a, s));
+        } else {
+            GemmArgs p3 = a3, p4 = a4;
+            if (P.g4.splits > 1) { p4.C = part_b; p4.partial_stride = (size_t)a4.M * a4.N; }
+            if (P.g3.splits > 1) { p3.C = part_a; p3.partial_stride = (size_t)a3.M * a3.N; }
+            HIP_TRY(launch_gemm(P.g4, true, true, P.g4.splits > 1 ? EPI_PARTIAL : EPI_TANHGRAD, p4, s));
+            HIP_TRY(launch_gemm(P.g3, false, false, P.g3.splits > 1 ? EPI_PARTIAL : EPI_AXPBY, p3, s));
+            MARK(4);
+            if (P.g4.splits > 1) HIP_TRY(launch_reduce(P.g4.splits, EPI_TANHGRAD, a4, part_b, s));
+            if (P.g3.splits > 1) HIP_TRY(launch_reduce(P.g3.splits, EPI_AXPBY, a3, part_a, s));
         }
-
         MARK(5);
-
-        // dA1 = (dO W2^T) * (1 - H*H)
-        a = GemmArgs{};
-        a.A = Z; a.lda = L.ldz; a.B = W2; a.ldb = n_out; a.C = dA1; a.ldc = L.ldh;
-        a.M = rows; a.N = n_hid; a.K = n_out; a.alpha = 1.f; a.beta = 0.f; a.aux = H; a.ldaux = L.ldh;
-        HIP_TRY(mlp_product(P.g4, true, true, EPI_TANHGRAD, a, partial, s));
-        MARK(6);
 
         // dW1 (+)= Xs^T dA1
         a = GemmArgs{};
         a.A = Xs; a.lda = n_in; a.B = dA1; a.ldb = L.ldh; a.C = dW1; a.ldc = n_hid;
         a.M = n_in; a.N = n_hid; a.K = rows; a.alpha = 1.f; a.beta = beta;
-        HIP_TRY(mlp_product(P.g5, false, false, EPI_AXPBY, a, partial, s));
+        if (P.g5.splits > 1) {
+            GemmArgs p5 = a;
+            p5.C = part_a; p5.partial_stride = (size_t)a.M * a.N;
+            HIP_TRY(launch_gemm(P.g5, false, false, EPI_PARTIAL, p5, s));
+            MARK(6);
+            HIP_TRY(launch_reduce(P.g5.splits, EPI_AXPBY, a, part_a, s));
+        } else {
+            HIP_TRY(launch_gemm(P.g5, false, false, EPI_AXPBY, a, s));
+            MARK(6);
+        }
         MARK(7);
+
+        // db2 (+)= 1^T dO,  db1 (+)= 1^T dA1
         if (biases) {
+            hipLaunchKernelGGL(column_sum_kernel, dim3((n_out + 63) / 64), dim3(256), 0, s, Z, L.ldz, rows, n_out,
+                               d->db2, beta);
             hipLaunchKernelGGL(column_sum_kernel, dim3((n_hid + 63) / 64), dim3(256), 0, s, dA1, L.ldh, rows,
                                n_hid, d->db1, beta);
             HIP_TRY(hipGetLastError());
@@ -366,7 +470,7 @@ int ulsnn_sgemm(char transa, char transb, int m, int n, int k, float alpha, cons
         return hipGetLastError() == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
     }
     if (!A || !B) return ULSNN_ERR_NULL;
-    const GemmPlan p = plan_gemm(m, n, k, false);
+    const GemmPlan p = plan_gemm(m, n, k, is_n(transa), is_t(transb), false, ALL_CFGS);
     GemmArgs a{};
     a.A = A; a.B = B; a.C = C; a.M = m; a.N = n; a.K = k; a.lda = lda; a.ldb = ldb; a.ldc = ldc;
     a.alpha = alpha; a.beta = beta;
@@ -433,6 +537,27 @@ int ulsnn_mlp_grad_timed(const ulsnn_mlp_desc *desc, const void *W1, const void 
             if (hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]) != hipSuccess) out = ULSNN_ERR_HIP;
     for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
     return out;
+}
+
+int ulsnn_mlp_grad_describe_plan(const ulsnn_mlp_desc *desc, int batch, char *buf, size_t buf_bytes)
+{
+    if (!desc || !buf) return ULSNN_ERR_NULL;
+    if (!desc_ok(desc) || batch < 1 || buf_bytes < 1) return ULSNN_ERR_DIM;
+    const MlpLayout L = mlp_layout(desc, batch);
+    const SlabPlans P = plan_slab(L, desc->n_in, desc->n_hid, desc->n_out, L.slab);
+    const GemmPlan *g[5] = {&P.g1, &P.g2, &P.g3, &P.g4, &P.g5};
+    const char *what[5] = {"hidden_layer", "output_layer", "dW2", "hidden_delta", "dW1"};
+    size_t used = 0;
+    int n = snprintf(buf, buf_bytes, "rows_per_pass=%d paired_backward=%d workspace_bytes=%zu\n", L.slab,
+                     (int)P.paired, L.bytes);
+    if (n > 0) used = std::min((size_t)n, buf_bytes - 1);
+    for (int i = 0; i < 5 && used + 1 < buf_bytes; ++i) {
+        n = snprintf(buf + used, buf_bytes - used, "%s: tile=%s tiles=%dx%d splits=%d kchunk=%d model_us=%.1f\n",
+                     what[i], CFG_INFO[g[i]->cfg].name, g[i]->tiles_m, g[i]->tiles_n, g[i]->splits, g[i]->kchunk,
+                     g[i]->est_us);
+        if (n > 0) used = std::min(used + (size_t)n, buf_bytes - 1);
+    }
+    return ULSNN_OK;
 }
 
 double ulsnn_sgemm_flops(int m, int n, int k) { return 2.0 * (double)m * (double)n * (double)k; }
