@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-sgemm", action="store_true", help="skip the standalone SGEMM sweep")
     ap.add_argument("--sgemm-sizes", type=int, nargs="*", default=[256, 1024, 4096, 8192])
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy kernel (reference for HBM byte counters)")
     return ap.parse_args()
 
 
@@ -154,6 +156,13 @@ def main():
         "frac_of_fp32_mfma_peak": round(gflops / (PEAK_FP32_MFMA_TFLOPS * 1e3), 4),
         "loss": loss, "stages": stages, "roofline": roofline,
     }
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                 # one elementwise copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_sgemm:
         result["sgemm"] = bench_sgemm(ulsnn, si, torch, args.sgemm_sizes)
     if not args.no_cpu:

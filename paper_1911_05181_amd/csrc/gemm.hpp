@@ -161,22 +161,32 @@ __device__ __forceinline__ floatx4 panel_read(const float *lds, int row, int s, 
     }
 }
 
-// Map the hardware workgroup id to a tile.  Consecutive ids are spread round-robin over the 8 XCDs (each with
-// its own L2), so each XCD is given a contiguous range of tiles, and inside it tiles are walked in groups of
-// GROUP_M tile rows so that the A and B panels a group touches stay in that L2.
-__device__ __forceinline__ void tile_of_workgroup(int pid, int tiles_m, int tiles_n, int &tm, int &tn)
+// Consecutive hardware workgroup ids are spread round-robin over the 8 XCDs (each with its own L2).  This maps
+// id -> position so that each XCD receives a CONTIGUOUS range of positions 0..n-1 (a bijection for any n).
+__device__ __forceinline__ int xcd_contiguous(int pid, int n)
 {
-    constexpr int XCDS = 8, GROUP_M = 8;
-    const int nt = tiles_m * tiles_n;
-    const int q = nt / XCDS, rem = nt % XCDS;
+    constexpr int XCDS = 8;
+    const int q = n / XCDS, rem = n % XCDS;
     const int xcd = pid % XCDS, loc = pid / XCDS;
-    const int lid = xcd * q + (xcd < rem ? xcd : rem) + loc;
+    return xcd * q + (xcd < rem ? xcd : rem) + loc;
+}
+
+// Tiles are walked in groups of GROUP_M tile rows, so that the A and B panels a group touches stay in L2.
+__device__ __forceinline__ void grouped_tile(int lid, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    constexpr int GROUP_M = 8;
     const int group = GROUP_M * tiles_n;
     const int gid = lid / group;
     const int first_m = gid * GROUP_M;
     const int gsz = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
     tm = first_m + (lid % group) % gsz;
     tn = (lid % group) / gsz;
+}
+
+// Map the hardware workgroup id of a plain launch to a tile: XCD-contiguous, then grouped.
+__device__ __forceinline__ void tile_of_workgroup(int pid, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    grouped_tile(xcd_contiguous(pid, tiles_m * tiles_n), tiles_m, tiles_n, tm, tn);
 }
 
 __device__ __forceinline__ float tanh_f32(float x)
@@ -286,11 +296,13 @@ constexpr int gemm_lds_floats()
     return 2 * (Panel<A_KC, Cfg::BM, Cfg::BK>::SIZE + Panel<B_KC, Cfg::BN, Cfg::BK>::SIZE);
 }
 
-// The work of one workgroup: tile number `pid` (before the XCD / group remapping) of k split `z`.
-// `lds` points at gemm_lds_floats() floats of 16-byte aligned LDS.
+// The product of one tile over the k range [kbeg, kend), followed by epilogue EPI written through `Cout`
+// (row stride ldc).  `lds` points at gemm_lds_floats() floats of 16-byte
+// aligned LDS; every thread of the workgroup must call this, and LDS is free again on return.
 template <class Cfg, bool A_KC, bool B_KC, int EPI>
-__device__ __forceinline__ void gemm_tile(const GemmArgs &g, const int pid, const int z, float *lds,
-                                          const int wg_linear)
+__device__ __forceinline__ void gemm_segment(const GemmArgs &g, const int tile_m, const int tile_n, const int kbeg,
+                                             const int kend, float *Cout, const int ldc, float *lds,
+                                             const int wg_linear)
 {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, THREADS = Cfg::THREADS;
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
@@ -309,11 +321,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const int pid, cons
     const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
     const int wrow = wm * Cfg::WTM, wcol = wn * Cfg::WTN;
 
-    int tile_m, tile_n;
-    tile_of_workgroup(pid, g.tiles_m, g.tiles_n, tile_m, tile_n);
     const int i0 = tile_m * BM, j0 = tile_n * BN;
-    const int kbeg = z * g.kchunk;
-    const int kend = (kbeg + g.kchunk < g.K) ? kbeg + g.kchunk : g.K;
     ULSNN_STAMP(0);
 #ifdef ULSNN_TRACE
     if (g.trace && threadIdx.x == 0) {
@@ -412,12 +420,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const int pid, cons
 
     ULSNN_STAMP(2);
     // Epilogue.  Accumulator register r of a 32x32 block holds row 8*(r/4) + 4*h + r%4, column lane%32.
-    float *Cout = g.C;
-    int ldc = g.ldc;
-    if (EPI == EPI_PARTIAL) {
-        Cout = g.C + (size_t)z * g.partial_stride;
-        ldc = g.N;
-    }
 #pragma unroll
     for (int y = 0; y < TN; ++y) {
         const int j = j0 + wn * Cfg::WTN + y * 32 + l32;
@@ -453,6 +455,24 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const int pid, cons
 #ifdef ULSNN_TRACE
     if (g.trace && threadIdx.x == 0) g.trace[(size_t)wg_linear * 8 + 7] = clock64();
 #endif
+}
+
+// The work of one workgroup of a plain launch: tile number `pid` (before the XCD / group remapping), k split `z`.
+template <class Cfg, bool A_KC, bool B_KC, int EPI>
+__device__ __forceinline__ void gemm_tile(const GemmArgs &g, const int pid, const int z, float *lds,
+                                          const int wg_linear)
+{
+    int tile_m, tile_n;
+    tile_of_workgroup(pid, g.tiles_m, g.tiles_n, tile_m, tile_n);
+    const int kbeg = z * g.kchunk;
+    const int kend = (kbeg + g.kchunk < g.K) ? kbeg + g.kchunk : g.K;
+    float *Cout = g.C;
+    int ldc = g.ldc;
+    if (EPI == EPI_PARTIAL) {
+        Cout = g.C + (size_t)z * g.partial_stride;
+        ldc = g.N;
+    }
+    gemm_segment<Cfg, A_KC, B_KC, EPI>(g, tile_m, tile_n, kbeg, kend, Cout, ldc, lds, wg_linear);
 }
 
 // One GEMM per launch: grid = (tiles, k splits).

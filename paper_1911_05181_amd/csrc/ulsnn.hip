@@ -17,7 +17,10 @@ using namespace ulsnn;
 namespace {
 
 constexpr int NUM_CU = 256;          // MI355X: 8 XCDs x 32 compute units
-constexpr int SLAB_ROWS = 16384;     // patterns processed per internal pass of the MLP gradient
+#ifndef ULSNN_SLAB_ROWS
+#define ULSNN_SLAB_ROWS 32768
+#endif
+constexpr int SLAB_ROWS = ULSNN_SLAB_ROWS;   // patterns processed per internal pass of the MLP gradient
 
 inline bool is_n(char t) { return t == 'N' || t == 'n'; }
 inline bool is_t(char t) { return t == 'T' || t == 't' || t == 'C' || t == 'c'; }

@@ -107,11 +107,35 @@ def test_mlp_grad_argument_errors():
 def test_workspace_query():
     w = ulsnn.mlp_grad_workspace_bytes
     assert w(400, 480, 3203, 0) == 0 and w(0, 480, 3203, 16) == 0
-    sizes = [w(400, 480, 3203, b) for b in (1, 100, 4096, 16384, 16385, 262144, 9_000_000)]
+    sizes = [w(400, 480, 3203, b) for b in (1, 100, 4096, 32768, 32769, 262144, 9_000_000)]
     assert all(a <= b for a, b in zip(sizes, sizes[1:]))         # non-decreasing in batch
-    assert sizes[-1] == sizes[-2] == sizes[-3]                   # constant above the slab size
+    assert sizes[-1] == sizes[-2] == sizes[-3] == sizes[-4]      # constant above the internal pass size
     assert sizes[2] >= 4096 * (3203 + 2 * 480) * 4               # holds Z, H and dA1 of the batch
     assert sizes[-1] < 1 << 30                                   # and stays modest for any batch
+
+
+def test_plan_description():
+    text = ulsnn.mlp_grad_describe_plan(400, 480, 3203, 4096)
+    lines = text.strip().splitlines()
+    assert lines[0].startswith("rows_per_pass=4096")
+    names = [l.split(":")[0] for l in lines[1:]]
+    assert names == ["hidden_layer", "output_layer", "dW2", "hidden_delta", "dW1"]      # the five products
+    for l in lines[1:]:
+        f = dict(kv.split("=") for kv in l.split(": ")[1].split())
+        tm, tn = (int(v) for v in f["tiles"].split("x"))
+        assert tm >= 1 and tn >= 1 and int(f["splits"]) >= 1 and float(f["model_us"]) > 0
+        assert int(f["splits"]) * int(f["kchunk"]) >= {"hidden_layer": 400, "output_layer": 480, "dW2": 4096,
+                                                        "hidden_delta": 3203, "dW1": 4096}[l.split(":")[0]]
+    # the weight-gradient products have few output tiles and a long k: they must be k-split to fill 256 CUs
+    split = {l.split(":")[0]: int(dict(kv.split("=") for kv in l.split(": ")[1].split())["splits"]) for l in lines[1:]}
+    assert split["dW2"] > 1 and split["dW1"] > 1 and split["hidden_layer"] == 1 and split["output_layer"] == 1
+    L = ulsnn.load()
+    import ctypes as C2
+    buf = C2.create_string_buffer(16)
+    d = _desc()
+    assert L.ulsnn_mlp_grad_describe_plan(C2.byref(d), 4096, buf, 16) == OK and len(buf.value) <= 15   # truncated
+    assert L.ulsnn_mlp_grad_describe_plan(None, 4096, buf, 16) == E_NULL
+    assert L.ulsnn_mlp_grad_describe_plan(C2.byref(d), 0, buf, 16) == E_DIM
 
 
 def test_binding_refuses_cpu_tensors():

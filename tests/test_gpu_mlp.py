@@ -142,8 +142,23 @@ def test_chunked_epoch_matches_oracle_and_single_call():
 
 def test_batch_larger_than_internal_slab():
     """A batch that the library splits into several internal passes (small net so the oracle stays quick)."""
-    p = _problem(si.MLP_SMALL, 0, 40_000, random_biases=True)
-    _compare(_gpu_grad(*p), _oracle_grad(*p), "64-32-10 B=40000")
+    p = _problem(si.MLP_SMALL, 0, 70_000, random_biases=True)
+    _compare(_gpu_grad(*p), _oracle_grad(*p), "64-32-10 B=70000")
+
+
+def test_timed_variant_matches_and_reports_stages():
+    p = _problem(si.MLP_JOCR, 2, 1024)
+    W1, W2, _, _, X, y = p
+    want = _gpu_grad(*p)
+    got, ms = ulsnn.mlp_grad_timed(_dev(W1), _dev(W2), _dev(X), _dev(y))
+    torch.cuda.synchronize()
+    assert torch.equal(got.dW1, want.dW1) and torch.equal(got.dW2, want.dW2) and torch.equal(got.loss, want.loss)
+    assert list(ms) == list(ulsnn.MLP_STAGES) and all(v >= 0 for v in ms.values())
+    assert ms["output_layer"] > 0 and ms["backward_products"] > 0
+    with pytest.raises(ulsnn.UlsnnError) as e:                       # more than one internal pass: refused
+        big = _problem(si.MLP_SMALL, 0, 40_000)
+        ulsnn.mlp_grad_timed(_dev(big[0]), _dev(big[1]), _dev(big[4]), _dev(big[5]))
+    assert e.value.status == 6
 
 
 def test_additivity_on_device():
