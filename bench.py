@@ -28,6 +28,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3      # 256 CUs x 256 flop/clk/CU x 2.4 GHz
+# HBM bytes per launch of the dominant kernel (paired backward products, batch 4096): rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB copy (2.000 and 1.000); 275.1 MB read,
+# 56.1 MB written.  Source: profiles/mlp_grad_b4096_hbm_traffic_pmc.md.  Algorithmic: 119.0 MB read, 54.3 MB written.
+PMC_TRAFFIC_BYTES = {"backward_products": 331.2e6}
 METRIC = "fp32 GFLOP/s (% of MFMA FP32 peak); MLP gradient patterns/sec"
 BATCH = 4096
 SEED = 2
@@ -143,7 +147,8 @@ def main():
     achieved = stage_flops[dom] / (acc[dom] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": f"fp32 MFMA GEMM launch of stage '{dom}'", "achieved": round(achieved, 2),
                 "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4),
-                "traffic": None, "flops_per_launch": stage_flops[dom], "avg_launch_ms": round(acc[dom], 4)}
+                "traffic": PMC_TRAFFIC_BYTES.get(dom), "traffic_unit": "bytes of HBM per launch (calibrated PMC)",
+                "flops_per_launch": stage_flops[dom], "avg_launch_ms": round(acc[dom], 4)}
 
     result = {
         "metric": METRIC, "value": round(gflops, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
