@@ -69,8 +69,14 @@ int ulsnn_sgemm(char transa, char transb, int m, int n, int k, float alpha, cons
  *   accumulate: 0 -> dW1, dW2, db1, db2 and loss are overwritten;
  *               1 -> the call ADDS to them (gradient and error are additive over patterns, section 4.3;
  *                    this is how an epoch is summed over chunks of patterns).
- *   operand_dtype: 0 = fp32 storage.  1 = bf16 storage of X, W1, W2 with fp32 accumulation: reserved,
- *                    returns ULSNN_ERR_UNSUPPORTED in this build.
+ *   operand_dtype: 0 = fp32 storage of W1, W2, X (the paper's precision; section 4.2 reports 32 bits to be enough).
+ *                  1 = bf16 storage (section 4.2 notes that 16 bits can suffice for small nets): W1, W2 and X point
+ *                      at bf16 values (upper 16 bits of an IEEE float, row-major, dense); H, dO and dA1 are kept in
+ *                      bf16 (round to nearest even) and multiplied on the bf16 matrix instructions; every product
+ *                      accumulates in fp32; logits, softmax, loss, dW1, dW2, db1, db2 (and b1, b2) stay fp32.
+ *                      Fastest when n_in and n_hid are multiples of 8 (16-byte rows); other sizes are correct but
+ *                      use an element-wise fetch for the operands whose rows are not 16-byte aligned (W1 and W2
+ *                      are re-laid out internally, X is not).  Any other value: ULSNN_ERR_UNSUPPORTED.
  *   workspace: device scratch of at least ulsnn_mlp_grad_workspace_bytes(desc, batch) bytes, 256-byte aligned.
  *     Its contents on entry do not matter and are undefined on return.  Two calls that may run concurrently
  *     (different streams) need different workspaces.
@@ -105,7 +111,8 @@ size_t ulsnn_mlp_grad_workspace_bytes(const ulsnn_mlp_desc *desc, int batch);
  *   squared error against a dense target matrix) is replaced by softmax / cross-entropy against integer labels.
  *   Counts batch * (4 n_in n_hid + 6 n_hid n_out) floating-point operations (section 6.2).
  *
- *   W1, W2, X [batch x n_in, dense row-major]: const device fp32.  labels[batch]: device int32; a label
+ *   W1, W2, X [batch x n_in, dense row-major]: const device fp32 (bf16 if desc->operand_dtype == 1).
+ *   labels[batch]: device int32; a label
  *   outside [0, n_out) marks a pattern that is ignored (zero delta, nothing added to the loss).
  *   dW1 [n_in x n_hid], dW2 [n_hid x n_out]: device fp32, dense.  loss: ONE device float.
  *   batch == 0 is valid: with accumulate == 0 the outputs are zeroed, with accumulate == 1 nothing changes.

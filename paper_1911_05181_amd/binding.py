@@ -124,9 +124,11 @@ def _desc(n_in, n_hid, n_out, b1, b2, db1, db2, accumulate, workspace, stream, o
     return d
 
 
-def mlp_grad_workspace_bytes(n_in: int, n_hid: int, n_out: int, batch: int) -> int:
+def mlp_grad_workspace_bytes(n_in: int, n_hid: int, n_out: int, batch: int, operand_dtype: int = 0) -> int:
+    """Workspace bytes for fp32 (operand_dtype 0) or bf16-stored (1) operands."""
     d = _MlpDesc()
     d.n_in, d.n_hid, d.n_out = n_in, n_hid, n_out
+    d.operand_dtype = operand_dtype
     return int(load().ulsnn_mlp_grad_workspace_bytes(C.byref(d), batch))
 
 
@@ -151,7 +153,16 @@ class MlpGradResult:
 
 
 def _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate):
-    _dev_f32(W1, "W1"), _dev_f32(W2, "W2"), _dev_f32(X, "X")
+    """Checks shapes and types; returns (n_in, n_hid, n_out, out, operand_dtype).  W1, W2 and X are all float32
+    (operand_dtype 0) or all bfloat16 (operand_dtype 1); gradients and loss are always float32."""
+    if W1.dtype == torch.bfloat16:
+        for t, nm in ((W1, "W1"), (W2, "W2"), (X, "X")):
+            if not (t.is_cuda and t.dtype == torch.bfloat16):
+                raise TypeError(f"{nm} must be a bfloat16 tensor on the GPU (W1 is bfloat16)")
+        operand_dtype = 1
+    else:
+        _dev_f32(W1, "W1"), _dev_f32(W2, "W2"), _dev_f32(X, "X")
+        operand_dtype = 0
     if not (labels.is_cuda and labels.dtype == torch.int32):
         raise TypeError("labels must be an int32 tensor on the GPU")
     for t in (W1, W2, X, labels):
@@ -167,21 +178,22 @@ def _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate):
         if accumulate:
             raise ValueError("accumulate=True needs the tensors to add to (out=...)")
         dev = W1.device
-        out = MlpGradResult(torch.empty_like(W1), torch.empty_like(W2), torch.empty(1, device=dev),
+        out = MlpGradResult(torch.empty(W1.shape, dtype=torch.float32, device=dev),
+                            torch.empty(W2.shape, dtype=torch.float32, device=dev), torch.empty(1, device=dev),
                             None if b1 is None else torch.empty_like(b1),
                             None if b2 is None else torch.empty_like(b2))
-    return n_in, n_hid, n_out, out
+    return n_in, n_hid, n_out, out, operand_dtype
 
 
 def mlp_grad(W1, W2, X, labels, b1=None, b2=None, *, out: Optional[MlpGradResult] = None, accumulate=False,
              workspace: Optional[torch.Tensor] = None, stream=None) -> MlpGradResult:
     """Loss and gradient of the MLP summed over the rows of X (ulsnn_mlp_grad).  Asynchronous on the stream."""
-    n_in, n_hid, n_out, out = _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate)
+    n_in, n_hid, n_out, out, odt = _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate)
     batch = X.shape[0]
     if workspace is None:
-        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch)
+        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch, odt)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
-    d = _desc(n_in, n_hid, n_out, b1, b2, out.db1, out.db2, accumulate, workspace, stream)
+    d = _desc(n_in, n_hid, n_out, b1, b2, out.db1, out.db2, accumulate, workspace, stream, odt)
     rc = load().ulsnn_mlp_grad(C.byref(d), _ptr(W1), _ptr(W2), _ptr(X), _ptr(labels), batch, _ptr(out.dW1),
                                _ptr(out.dW2), _ptr(out.loss))
     if rc:
@@ -197,12 +209,12 @@ def mlp_grad_timed(W1, W2, X, labels, b1=None, b2=None, *, out: Optional[MlpGrad
                    workspace: Optional[torch.Tensor] = None, stream=None):
     """ulsnn_mlp_grad_timed: the same work with HIP events at the stage boundaries.  Synchronises the stream.
     Returns (result, {stage name: milliseconds})."""
-    n_in, n_hid, n_out, out = _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate)
+    n_in, n_hid, n_out, out, odt = _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate)
     batch = X.shape[0]
     if workspace is None:
-        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch)
+        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch, odt)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
-    d = _desc(n_in, n_hid, n_out, b1, b2, out.db1, out.db2, accumulate, workspace, stream)
+    d = _desc(n_in, n_hid, n_out, b1, b2, out.db1, out.db2, accumulate, workspace, stream, odt)
     ms = (C.c_float * len(MLP_STAGES))()
     rc = load().ulsnn_mlp_grad_timed(C.byref(d), _ptr(W1), _ptr(W2), _ptr(X), _ptr(labels), batch, _ptr(out.dW1),
                                      _ptr(out.dW2), _ptr(out.loss), ms)
@@ -214,12 +226,12 @@ def mlp_grad_timed(W1, W2, X, labels, b1=None, b2=None, *, out: Optional[MlpGrad
 def mlp_grad_epoch(W1, W2, X, labels, chunk: int, b1=None, b2=None, *, out: Optional[MlpGradResult] = None,
                    accumulate=False, workspace: Optional[torch.Tensor] = None, stream=None) -> MlpGradResult:
     """Gradient over all rows of X taken `chunk` patterns at a time and summed (ulsnn_mlp_grad_epoch)."""
-    n_in, n_hid, n_out, out = _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate)
+    n_in, n_hid, n_out, out, odt = _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate)
     n = X.shape[0]
     if workspace is None:
-        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, min(max(chunk, 1), max(n, 1)))
+        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, min(max(chunk, 1), max(n, 1)), odt)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
-    d = _desc(n_in, n_hid, n_out, b1, b2, out.db1, out.db2, accumulate, workspace, stream)
+    d = _desc(n_in, n_hid, n_out, b1, b2, out.db1, out.db2, accumulate, workspace, stream, odt)
     rc = load().ulsnn_mlp_grad_epoch(C.byref(d), _ptr(W1), _ptr(W2), _ptr(X), _ptr(labels), n, chunk,
                                      _ptr(out.dW1), _ptr(out.dW2), _ptr(out.loss))
     if rc:

@@ -1,0 +1,364 @@
+// GEMM with bf16 operands and fp32 accumulation on the gfx950 matrix cores: C = epilogue(op(A) * op(B)).
+//
+// Same structure as the fp32 kernel (gemm.hpp): a BM x BN tile per workgroup, 32 x 32 accumulator blocks, a k loop
+// over two LDS stages with register prefetch of the next panels.  What differs:
+//   * the instruction is v_mfma_f32_32x32x16_bf16: each lane supplies EIGHT consecutive k of its row
+//     (k = 8*(lane/32) .. +7), so a step is BK = 32 deep and holds two such instructions per accumulator block;
+//   * an operand whose k is contiguous in memory ("KC") is kept row-major in LDS and read with one 16-byte read;
+//     an operand whose row/column index is contiguous ("MC") is kept k-major in LDS, exactly as it arrives, and
+//     read with the LDS transpose read (ds_read_b64_tr_b16), which hands each lane four consecutive k of its own
+//     row: transposition again costs no extra pass;
+//   * C is fp32 (logits, split-k partials, weight gradients) or bf16 rounded to nearest-even (hidden
+//     activations, hidden delta).
+// The fast global fetch needs 16-byte aligned rows (pointer and leading dimension multiples of 8 elements); the
+// host checks this and otherwise selects the element-wise checked fetch for every step (slow, but correct for any
+// 2-byte aligned operand).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "gemm.hpp"
+
+namespace ulsnn {
+
+typedef unsigned short u16;
+typedef u16 u16x8 __attribute__((ext_vector_type(8)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ float bf16_to_f32(u16 v) { return __uint_as_float((unsigned)v << 16); }
+
+// round to nearest, ties to even; NaN stays NaN
+__device__ __forceinline__ u16 f32_to_bf16(float x)
+{
+    unsigned u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u16)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (u16)(u >> 16);
+}
+
+struct Gemm16Args {
+    const u16 *A, *B;
+    void *C;               // float* or u16* (bf16), by epilogue
+    int M, N, K;
+    int lda, ldb, ldc;
+    float alpha, beta;
+    const float *bias;     // EPI_BIAS_TANH / EPI_BIAS, may be null
+    const u16 *aux;        // EPI_TANHGRAD: the tanh outputs (bf16), same shape as C
+    int ldaux;
+    int kchunk;            // k range per split (multiple of 32)
+    int tiles_m, tiles_n;
+    size_t partial_stride; // EPI_PARTIAL: elements between consecutive partial results
+    int aligned;           // 1: A and B rows are 16-byte aligned (fast vector fetch allowed)
+};
+
+template <int BM_, int BN_, int WM_, int WN_, int WAVES_PER_SIMD_ = 1>
+struct Tile16 {
+    static constexpr int BM = BM_, BN = BN_, BK = 32, WM = WM_, WN = WN_, WAVES_PER_SIMD = WAVES_PER_SIMD_;
+    static constexpr int THREADS = WM * WN * 64;
+    static constexpr int WTM = BM / WM, WTN = BN / WN;
+    static constexpr int TM = WTM / 32, TN = WTN / 32;
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "tile shape");
+};
+
+// LDS footprint (bf16 elements) of one stage of one operand panel; row lengths keep 16-byte (KC) / 8-byte (MC)
+// alignment of every read
+template <bool KC, int R>
+struct Panel16 {
+    static constexpr int LD = KC ? (32 + 8) : (R + 8);
+    static constexpr int SIZE = KC ? R * LD : 32 * LD;
+};
+
+__device__ __forceinline__ u16x8 load8_aligned(const u16 *p) { return *reinterpret_cast<const u16x8 *>(p); }
+
+// Checked element-wise fetch of this thread's share of a panel (rows r0.., k from k0, valid k < kend).
+template <bool KC, int R, int THREADS, int NV>
+__device__ __forceinline__ void panel16_fetch_checked(u16x8 (&reg)[NV], const u16 *__restrict__ P, int ld, int r0,
+                                                      int rmax, int k0, int kend, int tid)
+{
+    constexpr int TOTAL = R * 32 / 8;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int f = tid + v * THREADS;
+        u16x8 val = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (TOTAL % THREADS == 0 || f < TOTAL) {
+            if (KC) {
+                const int row = f / 4, kq = (f % 4) * 8;
+                const int gr = r0 + row, gk = k0 + kq;
+                if (gr < rmax) {
+                    const u16 *src = P + (size_t)gr * ld + gk;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (gk + e < kend) val[e] = src[e];
+                }
+            } else {
+                const int krow = f / (R / 8), rq = (f % (R / 8)) * 8;
+                const int gk = k0 + krow, gr = r0 + rq;
+                if (gk < kend) {
+                    const u16 *src = P + (size_t)gk * ld + gr;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (gr + e < rmax) val[e] = src[e];
+                }
+            }
+        }
+        reg[v] = val;
+    }
+}
+
+template <bool KC, int R, int THREADS, int NV>
+__device__ __forceinline__ void panel16_store(u16 *lds, const u16x8 (&reg)[NV], int tid)
+{
+    constexpr int TOTAL = R * 32 / 8;
+    constexpr int LD = Panel16<KC, R>::LD;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int f = tid + v * THREADS;
+        if (TOTAL % THREADS == 0 || f < TOTAL) {
+            const int off = KC ? (f / 4) * LD + (f % 4) * 8 : (f / (R / 8)) * LD + (f % (R / 8)) * 8;
+            *reinterpret_cast<u16x8 *>(lds + off) = reg[v];
+        }
+    }
+}
+
+// Unchecked 16-byte fetch for full k steps of aligned operands (see FastFetch in gemm.hpp for the edge rules).
+template <bool KC, int R, int THREADS, int NV>
+struct FastFetch16 {
+    unsigned off[NV];
+    unsigned edge;
+    int valid;
+
+    __device__ __forceinline__ void init(int ld, int r0, int rmax, int tid)
+    {
+        constexpr int TOTAL = R * 32 / 8;
+        edge = 0;
+        valid = rmax - r0;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            int f = tid + v * THREADS;
+            if (TOTAL % THREADS != 0 && f >= TOTAL) f = 0;
+            if (KC) {
+                int row = f / 4;
+                const int kq = (f % 4) * 8;
+                row = row < valid ? row : valid - 1;
+                off[v] = (unsigned)row * (unsigned)ld + (unsigned)kq;
+            } else {
+                const int krow = f / (R / 8);
+                int rq = (f % (R / 8)) * 8;
+                if (rq >= valid) rq = 0;
+                else if (rq + 7 >= valid) edge |= 1u << v;
+                off[v] = (unsigned)krow * (unsigned)ld + (unsigned)rq;
+            }
+        }
+    }
+
+    __device__ __forceinline__ void fetch(u16x8 (&reg)[NV], const u16 *__restrict__ base, int tid) const
+    {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const u16 *src = base + off[v];
+            if (KC || !(edge >> v & 1)) {
+                reg[v] = load8_aligned(src);
+            } else {
+                const int rq = ((tid + v * THREADS) % (R / 8)) * 8;
+                u16x8 val = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (rq + e < valid) val[e] = src[e];
+                reg[v] = val;
+            }
+        }
+    }
+};
+
+// The eight consecutive k (k = 16*ks + 8*(lane/32) .. +7) of row `row + lane%32` for one 32x32x16 instruction.
+template <bool KC, int R>
+__device__ __forceinline__ bf16x8 panel16_read(const u16 *lds, int row, int ks, int lane)
+{
+    constexpr int LD = Panel16<KC, R>::LD;
+    const int l32 = lane & 31, h = lane >> 5;
+    u16x8 raw;
+    if (KC) {
+        raw = *reinterpret_cast<const u16x8 *>(lds + (row + l32) * LD + ks * 16 + h * 8);
+    } else {
+        // Transpose read: within each group of 16 lanes, lane s supplies the address of a chunk of four
+        // consecutive rows at ONE k, and receives element s%4 of the chunks supplied by lanes s/4 + 4e, e = 0..3.
+        // With lane s pointing at (k0 + s/4, rows 4*(s%4)..+3), lane j ends up with row j at k0 .. k0+3.
+        const int s = lane & 15, g = (lane >> 4) & 1;
+        const u16 *p = lds + (ks * 16 + h * 8 + (s >> 2)) * LD + row + 16 * g + 4 * (s & 3);
+        typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
+        const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(p));
+        const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(p + 4 * LD));
+        raw = u16x8{(u16)lo.x, (u16)lo.y, (u16)lo.z, (u16)lo.w, (u16)hi.x, (u16)hi.y, (u16)hi.z, (u16)hi.w};
+    }
+    return __builtin_bit_cast(bf16x8, raw);
+}
+
+template <class Cfg, bool A_KC, bool B_KC>
+constexpr int gemm16_lds_elems()
+{
+    return 2 * (Panel16<A_KC, Cfg::BM>::SIZE + Panel16<B_KC, Cfg::BN>::SIZE);
+}
+
+// OUT_BF16: C is bf16 (EPI_BIAS_TANH, EPI_TANHGRAD) else fp32.
+template <class Cfg, bool A_KC, bool B_KC, int EPI>
+__device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int pid, const int z, u16 *lds)
+{
+    constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = 32, THREADS = Cfg::THREADS;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN;
+    constexpr bool OUT_BF16 = (EPI == EPI_BIAS_TANH || EPI == EPI_TANHGRAD);
+    using PA = Panel16<A_KC, BM>;
+    using PB = Panel16<B_KC, BN>;
+    constexpr int NVA = (BM * BK / 8 + THREADS - 1) / THREADS;
+    constexpr int NVB = (BN * BK / 8 + THREADS - 1) / THREADS;
+
+    auto stage_a = [&](int st) { return lds + st * PA::SIZE; };
+    auto stage_b = [&](int st) { return lds + 2 * PA::SIZE + st * PB::SIZE; };
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
+    const int wrow = wm * Cfg::WTM, wcol = wn * Cfg::WTN;
+
+    int tile_m, tile_n;
+    tile_of_workgroup(pid, g.tiles_m, g.tiles_n, tile_m, tile_n);
+    const int i0 = tile_m * BM, j0 = tile_n * BN;
+    const int kbeg = z * g.kchunk;
+    const int kend = (kbeg + g.kchunk < g.K) ? kbeg + g.kchunk : g.K;
+    // without 16-byte aligned rows every step goes through the checked fetch
+    const int nfull = g.aligned ? (kend - kbeg) / BK : 0;
+    const int nkb = (kend - kbeg + BK - 1) / BK;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    FastFetch16<A_KC, BM, THREADS, NVA> fa;
+    FastFetch16<B_KC, BN, THREADS, NVB> fb;
+    fa.init(g.lda, i0, g.M, tid);
+    fb.init(g.ldb, j0, g.N, tid);
+    const u16 *pa = A_KC ? g.A + (size_t)i0 * g.lda + kbeg : g.A + (size_t)kbeg * g.lda + i0;
+    const u16 *pb = B_KC ? g.B + (size_t)j0 * g.ldb + kbeg : g.B + (size_t)kbeg * g.ldb + j0;
+    const size_t step_a = A_KC ? (size_t)BK : (size_t)BK * g.lda;
+    const size_t step_b = B_KC ? (size_t)BK : (size_t)BK * g.ldb;
+
+    u16x8 ra[NVA], rb[NVB];
+#pragma unroll
+    for (int v = 0; v < NVA; ++v) ra[v] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int v = 0; v < NVB; ++v) rb[v] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+
+    if (nkb > 0) {
+        if (nfull > 0) {
+            fa.fetch(ra, pa, tid);
+            fb.fetch(rb, pb, tid);
+        } else {
+            panel16_fetch_checked<A_KC, BM, THREADS, NVA>(ra, g.A, g.lda, i0, g.M, kbeg, kend, tid);
+            panel16_fetch_checked<B_KC, BN, THREADS, NVB>(rb, g.B, g.ldb, j0, g.N, kbeg, kend, tid);
+        }
+        panel16_store<A_KC, BM, THREADS, NVA>(stage_a(0), ra, tid);
+        panel16_store<B_KC, BN, THREADS, NVB>(stage_b(0), rb, tid);
+    }
+    __syncthreads();
+
+    auto compute = [&](int cur) {
+        const u16 *la = stage_a(cur), *lb = stage_b(cur);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 a[TM], b[TN];
+#pragma unroll
+            for (int x = 0; x < TM; ++x) a[x] = panel16_read<A_KC, BM>(la, wrow + x * 32, ks, lane);
+#pragma unroll
+            for (int y = 0; y < TN; ++y) b[y] = panel16_read<B_KC, BN>(lb, wcol + y * 32, ks, lane);
+#pragma unroll
+            for (int x = 0; x < TM; ++x)
+#pragma unroll
+                for (int y = 0; y < TN; ++y)
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[x], b[y], acc[x][y], 0, 0, 0);
+        }
+    };
+
+    int kb = 0;
+    for (; kb + 1 < nfull; ++kb) {
+        const int cur = kb & 1;
+        pa += step_a;
+        pb += step_b;
+        fa.fetch(ra, pa, tid);
+        fb.fetch(rb, pb, tid);
+        compute(cur);
+        panel16_store<A_KC, BM, THREADS, NVA>(stage_a(cur ^ 1), ra, tid);
+        panel16_store<B_KC, BN, THREADS, NVB>(stage_b(cur ^ 1), rb, tid);
+        __syncthreads();
+    }
+    for (; kb < nkb; ++kb) {
+        const int cur = kb & 1;
+        const bool more = kb + 1 < nkb;
+        if (more) {
+            const int k0 = kbeg + (kb + 1) * BK;
+            panel16_fetch_checked<A_KC, BM, THREADS, NVA>(ra, g.A, g.lda, i0, g.M, k0, kend, tid);
+            panel16_fetch_checked<B_KC, BN, THREADS, NVB>(rb, g.B, g.ldb, j0, g.N, k0, kend, tid);
+        }
+        compute(cur);
+        if (more) {
+            panel16_store<A_KC, BM, THREADS, NVA>(stage_a(cur ^ 1), ra, tid);
+            panel16_store<B_KC, BN, THREADS, NVB>(stage_b(cur ^ 1), rb, tid);
+        }
+        __syncthreads();
+    }
+
+    // Epilogue: accumulator register r of a block holds row 8*(r/4) + 4*h + r%4, column lane%32.
+    float *Cf = (float *)g.C;
+    u16 *Ch = (u16 *)g.C;
+    int ldc = g.ldc;
+    if (EPI == EPI_PARTIAL) {
+        Cf += (size_t)z * g.partial_stride;
+        ldc = g.N;
+    }
+#pragma unroll
+    for (int y = 0; y < TN; ++y) {
+        const int j = j0 + wcol + y * 32 + l32;
+        if (j >= g.N) continue;
+        float bias = 0.f;
+        if ((EPI == EPI_BIAS_TANH || EPI == EPI_BIAS) && g.bias) bias = g.bias[j];
+#pragma unroll
+        for (int x = 0; x < TM; ++x) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = i0 + wrow + x * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                if (i >= g.M) continue;
+                const float v = acc[x][y][r];
+                const size_t at = (size_t)i * ldc + j;
+                if (EPI == EPI_AXPBY) {
+                    float out = g.alpha * v;
+                    if (g.beta != 0.f) out += g.beta * Cf[at];
+                    Cf[at] = out;
+                } else if (EPI == EPI_PARTIAL) {
+                    Cf[at] = v;
+                } else if (EPI == EPI_BIAS_TANH) {
+                    Ch[at] = f32_to_bf16(tanh_f32(v + bias));
+                } else if (EPI == EPI_BIAS) {
+                    Cf[at] = v + bias;
+                } else {
+                    const float hv = bf16_to_f32(g.aux[(size_t)i * g.ldaux + j]);
+                    Ch[at] = f32_to_bf16(v * (1.0f - hv * hv));
+                }
+            }
+        }
+    }
+    (void)OUT_BF16;
+}
+
+template <class Cfg, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm16_kernel(const Gemm16Args g)
+{
+    __shared__ __attribute__((aligned(16))) u16 lds[gemm16_lds_elems<Cfg, A_KC, B_KC>()];
+    gemm16_tile<Cfg, A_KC, B_KC, EPI>(g, blockIdx.x, blockIdx.y, lds);
+}
+
+}  // namespace ulsnn

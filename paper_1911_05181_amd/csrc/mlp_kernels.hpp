@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "gemm_bf16.hpp"   // u16, bf16_to_f32, f32_to_bf16
+
 namespace ulsnn {
 
 __device__ __forceinline__ float wave_max(float v)
@@ -55,10 +57,12 @@ __device__ __forceinline__ float block_sum(float v, float *red)
 //     z_c <- p_c - [c == label]            (the output delta; zero row if the label is out of range)
 //     row_loss[r] = m + ln s - z_label     (0 if the label is out of range)
 // The row is read from HBM once into registers (PER values per thread), so Z is read once and written once.
-template <int THREADS, int PER>
+// With OUT_BF16 the delta is written, rounded to bf16, to `out16` (row stride ld16) and Z is left untouched.
+template <int THREADS, int PER, bool OUT_BF16 = false>
 __global__ __launch_bounds__(THREADS) void softmax_ce_kernel(float *__restrict__ Z, int ldz, int n,
                                                              const int32_t *__restrict__ labels,
-                                                             float *__restrict__ row_loss)
+                                                             float *__restrict__ row_loss,
+                                                             u16 *__restrict__ out16 = nullptr, int ld16 = 0)
 {
     __shared__ float red[THREADS / 64];
     const int r = blockIdx.x;
@@ -88,15 +92,20 @@ __global__ __launch_bounds__(THREADS) void softmax_ce_kernel(float *__restrict__
 #pragma unroll
     for (int e = 0; e < PER; ++e) {
         const int c = threadIdx.x + e * THREADS;
-        if (c < n) z[c] = labelled ? v[e] * inv - (c == y ? 1.0f : 0.0f) : 0.0f;
+        if (c < n) {
+            const float d = labelled ? v[e] * inv - (c == y ? 1.0f : 0.0f) : 0.0f;
+            if (OUT_BF16) out16[(size_t)r * ld16 + c] = f32_to_bf16(d);
+            else z[c] = d;
+        }
     }
 }
 
 // Same operation for rows too long for registers: three passes over the row (the re-reads hit in cache).
-template <int THREADS>
+template <int THREADS, bool OUT_BF16 = false>
 __global__ __launch_bounds__(THREADS) void softmax_ce_long_kernel(float *__restrict__ Z, int ldz, int n,
                                                                   const int32_t *__restrict__ labels,
-                                                                  float *__restrict__ row_loss)
+                                                                  float *__restrict__ row_loss,
+                                                                  u16 *__restrict__ out16 = nullptr, int ld16 = 0)
 {
     __shared__ float red[THREADS / 64];
     const int r = blockIdx.x;
@@ -112,31 +121,70 @@ __global__ __launch_bounds__(THREADS) void softmax_ce_long_kernel(float *__restr
     const float inv = 1.0f / s;
     if (threadIdx.x == 0) row_loss[r] = labelled ? (m + __logf(s)) - z[y] : 0.f;
     __syncthreads();
-    for (int c = threadIdx.x; c < n; c += THREADS)
-        z[c] = labelled ? __expf(z[c] - m) * inv - (c == y ? 1.0f : 0.0f) : 0.0f;
+    for (int c = threadIdx.x; c < n; c += THREADS) {
+        const float d = labelled ? __expf(z[c] - m) * inv - (c == y ? 1.0f : 0.0f) : 0.0f;
+        if (OUT_BF16) out16[(size_t)r * ld16 + c] = f32_to_bf16(d);
+        else z[c] = d;
+    }
 }
 
 // out = alpha * sum_z partial[z] + beta * out over an M x N matrix (partials dense, ld = N; out with ldc).
-// With MUL_TANHGRAD the sum is multiplied by (1 - aux^2) first (hidden delta after a split-k product).
-template <bool MUL_TANHGRAD>
+// With MUL_TANHGRAD the sum is multiplied by (1 - aux^2) first (hidden delta after a split-k product); with BF16
+// (hidden delta of the bf16-operand path) aux and out are bf16 and the result is rounded to nearest-even.
+template <bool MUL_TANHGRAD, bool BF16 = false>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, size_t stride,
-                                                            int splits, float *__restrict__ out, int M, int N,
+                                                            int splits, void *__restrict__ out_v, int M, int N,
                                                             int ldc, float alpha, float beta,
-                                                            const float *__restrict__ aux, int ldaux)
+                                                            const void *__restrict__ aux_v, int ldaux)
 {
+    float *out = (float *)out_v;
+    const float *aux = (const float *)aux_v;
     const size_t total = (size_t)M * N;
     for (size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (size_t)gridDim.x * 256) {
         float s = 0.f;
         for (int zz = 0; zz < splits; ++zz) s += partial[(size_t)zz * stride + idx];   // fixed order
         const int i = (int)(idx / N), j = (int)(idx % N);
         if (MUL_TANHGRAD) {
-            const float hv = aux[(size_t)i * ldaux + j];
+            const float hv = BF16 ? bf16_to_f32(((const u16 *)aux_v)[(size_t)i * ldaux + j]) : aux[(size_t)i * ldaux + j];
             s *= (1.0f - hv * hv);
         }
-        float *dst = out + (size_t)i * ldc + j;
-        float o = alpha * s;
-        if (beta != 0.f) o += beta * *dst;
-        *dst = o;
+        if (BF16) {
+            ((u16 *)out_v)[(size_t)i * ldc + j] = f32_to_bf16(alpha * s);
+        } else {
+            float *dst = out + (size_t)i * ldc + j;
+            float o = alpha * s;
+            if (beta != 0.f) o += beta * *dst;
+            *dst = o;
+        }
+    }
+}
+
+// dst[r][0..cols) = src[r][0..cols) for 2-byte elements with different row strides (repack to aligned rows).
+__global__ __launch_bounds__(256) void repack16_kernel(const u16 *__restrict__ src, int ld_src, u16 *__restrict__ dst,
+                                                       int ld_dst, int rows, int cols)
+{
+    const size_t total = (size_t)rows * cols;
+    for (size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (size_t)gridDim.x * 256) {
+        const size_t r = idx / cols, c = idx % cols;
+        dst[r * ld_dst + c] = src[r * ld_src + c];
+    }
+}
+
+// out[c] = beta*out[c] + sum_r D[r][c] for a bf16 R x N matrix (bias gradients of the bf16-operand path).
+__global__ __launch_bounds__(256) void column_sum16_kernel(const u16 *__restrict__ D, int ld, int R, int N,
+                                                           float *__restrict__ out, float beta)
+{
+    __shared__ float red[4][64];
+    const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int phase = threadIdx.x >> 6;
+    float s = 0.f;
+    if (c < N)
+        for (int r = phase; r < R; r += 4) s += bf16_to_f32(D[(size_t)r * ld + c]);
+    red[phase][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (phase == 0 && c < N) {
+        const float t = ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
+        out[c] = (beta != 0.f ? beta * out[c] : 0.f) + t;
     }
 }
 

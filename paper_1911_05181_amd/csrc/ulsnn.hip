@@ -10,6 +10,7 @@
 #include <cstdio>
 
 #include "gemm.hpp"
+#include "gemm_bf16.hpp"
 #include "mlp_kernels.hpp"
 
 using namespace ulsnn;
@@ -74,7 +75,7 @@ inline double simd_utilisation(double w)
 // Estimated run time of one launch (+ the split-k reduction), in microseconds.  Not a simulator: a consistent
 // way to trade tile efficiency against how evenly the workgroups fill 256 compute units.
 double model_us(const CfgInfo &c, bool a_kc, bool b_kc, int m, int n, int k, int splits, int *kchunk_out,
-                int *splits_out)
+                int *splits_out, double peak_flops = 155.0e12)
 {
     const int chunk = (int)round_up((size_t)(k + splits - 1) / splits, c.bk);
     const int sp = (k + chunk - 1) / chunk;
@@ -83,7 +84,7 @@ double model_us(const CfgInfo &c, bool a_kc, bool b_kc, int m, int n, int k, int
     const long tiles = (long)((m + c.bm - 1) / c.bm) * ((n + c.bn - 1) / c.bn);
     const long wgs = tiles * sp;
     const double layout = (!a_kc && !b_kc) ? 0.92 : (a_kc && b_kc) ? 1.0 : 0.97;   // 4-byte LDS reads cost more
-    const double cu_rate = 155.0e12 / NUM_CU * c.eff * layout;                     // flop/s of one compute unit
+    const double cu_rate = peak_flops / NUM_CU * c.eff * layout;                   // flop/s of one compute unit
     const double flops_wg = 2.0 * c.bm * c.bn * (double)chunk;
     const double wps = c.threads / 256.0;                                          // wavefronts per SIMD per WG
     const long slots = (long)NUM_CU * c.occ;
@@ -233,6 +234,84 @@ hipError_t launch_reduce(int splits, int epi, const GemmArgs &a, const float *pa
 }
 
 // ---------------------------------------------------------------------------------------------------------
+// bf16-operand GEMM dispatch (fp32 accumulation): two tile shapes, same cost model with the measured bf16 rate
+// ---------------------------------------------------------------------------------------------------------
+
+using T16_128 = Tile16<128, 128, 2, 2, 3>;   // 256 threads, 3 workgroups / CU
+using T16_64 = Tile16<64, 64, 2, 2, 8>;      // 256 threads, 8 workgroups / CU
+
+enum Cfg16Id { CFG16_128 = 0, CFG16_64, CFG16_COUNT };
+
+constexpr CfgInfo CFG16_INFO[CFG16_COUNT] = {
+    {128, 128, 32, 256, 3, 1.00, "bf16 128x128"},
+    {64, 64, 32, 256, 8, 0.70, "bf16 64x64"},
+};
+constexpr double BF16_SUSTAINED_FLOPS = 800.0e12;   // what the 128x128 bf16 tile sustains on large problems
+
+struct Gemm16Plan {
+    Cfg16Id cfg;
+    int tiles_m, tiles_n;
+    int splits, kchunk;
+    double est_us;
+};
+
+Gemm16Plan plan_gemm16(int m, int n, int k, bool a_kc, bool b_kc, bool allow_split, size_t max_partial_floats)
+{
+    Gemm16Plan best{};
+    best.est_us = 1e30;
+    for (int ci = 0; ci < CFG16_COUNT; ++ci) {
+        const CfgInfo &c = CFG16_INFO[ci];
+        int max_splits = allow_split ? std::max(1, std::min(64, k / (8 * c.bk))) : 1;
+        if ((size_t)m * n > 0) max_splits = (int)std::min<size_t>(max_splits, std::max<size_t>(1, max_partial_floats / ((size_t)m * n)));
+        for (int s = 1; s <= max_splits; ++s) {
+            int chunk, sp;
+            const double us = model_us(c, a_kc, b_kc, m, n, std::max(k, 1), s, &chunk, &sp, BF16_SUSTAINED_FLOPS);
+            if (sp != s) continue;
+            if (us < best.est_us) {
+                best.cfg = (Cfg16Id)ci;
+                best.tiles_m = (m + c.bm - 1) / c.bm;
+                best.tiles_n = (n + c.bn - 1) / c.bn;
+                best.splits = sp;
+                best.kchunk = chunk;
+                best.est_us = us;
+            }
+        }
+    }
+    return best;
+}
+
+template <class Cfg, bool A_KC, bool B_KC, int EPI>
+hipError_t launch16_one(const Gemm16Args &a, int splits, hipStream_t s)
+{
+    const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)splits);
+    hipLaunchKernelGGL((gemm16_kernel<Cfg, A_KC, B_KC, EPI>), grid, dim3(Cfg::THREADS), 0, s, a);
+    return hipGetLastError();
+}
+
+inline bool rows_16b_aligned(const void *p, int ld) { return ((uintptr_t)p & 15) == 0 && (ld & 7) == 0; }
+
+// The combinations the MLP gradient needs: NN with bias+tanh / bias, NT with the tanh' mask, NT and TN partials,
+// TN with alpha/beta.
+hipError_t launch_gemm16(const Gemm16Plan &p, bool a_kc, bool b_kc, int epi, Gemm16Args a, hipStream_t s)
+{
+    a.tiles_m = p.tiles_m;
+    a.tiles_n = p.tiles_n;
+    a.kchunk = p.kchunk;
+    a.aligned = rows_16b_aligned(a.A, a.lda) && rows_16b_aligned(a.B, a.ldb);
+    auto go = [&](auto cfg) -> hipError_t {
+        using Cfg = decltype(cfg);
+        if (epi == EPI_BIAS_TANH && a_kc && !b_kc) return launch16_one<Cfg, true, false, EPI_BIAS_TANH>(a, p.splits, s);
+        if (epi == EPI_BIAS && a_kc && !b_kc) return launch16_one<Cfg, true, false, EPI_BIAS>(a, p.splits, s);
+        if (epi == EPI_TANHGRAD && a_kc && b_kc) return launch16_one<Cfg, true, true, EPI_TANHGRAD>(a, p.splits, s);
+        if (epi == EPI_PARTIAL && a_kc && b_kc) return launch16_one<Cfg, true, true, EPI_PARTIAL>(a, p.splits, s);
+        if (epi == EPI_PARTIAL && !a_kc && !b_kc) return launch16_one<Cfg, false, false, EPI_PARTIAL>(a, p.splits, s);
+        if (epi == EPI_AXPBY && !a_kc && !b_kc) return launch16_one<Cfg, false, false, EPI_AXPBY>(a, p.splits, s);
+        return hipErrorInvalidValue;
+    };
+    return p.cfg == CFG16_128 ? go(T16_128{}) : go(T16_64{});
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // MLP gradient: plans and workspace layout for one slab of patterns
 // ---------------------------------------------------------------------------------------------------------
 
@@ -240,9 +319,11 @@ constexpr size_t PARTIAL_CAP_FLOATS = (size_t)16 << 20;   // at most 64 MiB of s
 
 struct MlpLayout {
     int slab;                       // rows per pass
-    int ldh, ldz;                   // row strides of H / dA1 and of Z / dO
+    int ldh, ldz;                   // row strides (elements) of H / dA1 and of Z / dO
+    int ldw1p, ldw2p;               // bf16 path: row strides of the 16-byte aligned copies of W1 and W2
     size_t floats_pa, floats_pb;    // split-k partial regions: A (dW2, then dW1) and B (hidden delta)
     size_t off_h, off_z, off_da1, off_rowloss, off_pa, off_pb, bytes;
+    size_t off_do16, off_w1p, off_w2p;   // bf16 path only
 };
 
 struct SlabPlans {
@@ -259,21 +340,30 @@ bool desc_ok(const ulsnn_mlp_desc *d)
 // workspace sized for a batch also serves every smaller one.
 MlpLayout mlp_layout(const ulsnn_mlp_desc *d, int batch)
 {
-    MlpLayout L;
+    MlpLayout L{};
+    const bool bf16 = d->operand_dtype == 1;
+    const size_t act = bf16 ? 2 : 4;               // bytes per stored activation (H, dA1)
     L.slab = std::max(1, std::min(batch, SLAB_ROWS));
     L.ldh = (int)round_up((size_t)d->n_hid, 32);
     L.ldz = (int)round_up((size_t)d->n_out, 32);
+    L.ldw1p = (int)round_up((size_t)d->n_hid, 8);
+    L.ldw2p = (int)round_up((size_t)d->n_out, 8);
     const size_t mn3 = (size_t)d->n_hid * d->n_out, mn5 = (size_t)d->n_in * d->n_hid;
     const size_t mn4 = (size_t)L.slab * d->n_hid;
     L.floats_pa = std::max(std::max(mn3, mn5), std::min(PARTIAL_CAP_FLOATS, 64 * std::max(mn3, mn5)));
     L.floats_pb = std::max(mn4, std::min(PARTIAL_CAP_FLOATS, 16 * mn4));
     size_t off = 0;
-    L.off_h = off;        off += round_up((size_t)L.slab * L.ldh * 4, 256);
+    L.off_h = off;        off += round_up((size_t)L.slab * L.ldh * act, 256);
     L.off_z = off;        off += round_up((size_t)L.slab * L.ldz * 4, 256);
-    L.off_da1 = off;      off += round_up((size_t)L.slab * L.ldh * 4, 256);
+    L.off_da1 = off;      off += round_up((size_t)L.slab * L.ldh * act, 256);
     L.off_rowloss = off;  off += round_up((size_t)L.slab * 4, 256);
     L.off_pa = off;       off += round_up(L.floats_pa * 4, 256);
     L.off_pb = off;       off += round_up(L.floats_pb * 4, 256);
+    if (bf16) {
+        L.off_do16 = off; off += round_up((size_t)L.slab * L.ldz * 2, 256);
+        L.off_w1p = off;  off += round_up((size_t)d->n_in * L.ldw1p * 2, 256);
+        L.off_w2p = off;  off += round_up((size_t)d->n_hid * L.ldw2p * 2, 256);
+    }
     L.bytes = off;
     return L;
 }
@@ -309,7 +399,7 @@ int check_mlp_args(const ulsnn_mlp_desc *d, const void *W1, const void *W2, cons
     const int nb = (d->b1 != nullptr) + (d->b2 != nullptr) + (d->db1 != nullptr) + (d->db2 != nullptr);
     if (nb != 0 && nb != 4) return ULSNN_ERR_NULL;
     if (d->accumulate != 0 && d->accumulate != 1) return ULSNN_ERR_UNSUPPORTED;
-    if (d->operand_dtype != 0) return ULSNN_ERR_UNSUPPORTED;
+    if (d->operand_dtype != 0 && d->operand_dtype != 1) return ULSNN_ERR_UNSUPPORTED;
     return ULSNN_OK;
 }
 
@@ -323,7 +413,11 @@ int check_mlp_args(const ulsnn_mlp_desc *d, const void *W1, const void *W2, cons
     } while (0)
 
 // `ev`, if not null, is an array of ULSNN_MLP_STAGES + 1 events recorded at the stage boundaries.
-int mlp_grad_impl(const ulsnn_mlp_desc *d, const float *W1, const float *W2, const float *X,
+int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const u16 *X, const int32_t *labels,
+                    int batch, float *dW1, float *dW2, float *loss, bool accumulate, hipEvent_t *ev);
+
+// W1v, W2v, Xv point at fp32 (operand_dtype 0) or bf16 (operand_dtype 1) data.
+int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, const void *Xv,
                   const int32_t *labels, int batch, float *dW1, float *dW2, float *loss, bool accumulate,
                   hipEvent_t *ev = nullptr)
 {
@@ -346,6 +440,11 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const float *W1, const float *W2, con
         }
         return ULSNN_OK;
     }
+
+    if (d->operand_dtype == 1)
+        return mlp_grad_impl16(d, (const u16 *)W1v, (const u16 *)W2v, (const u16 *)Xv, labels, batch, dW1, dW2, loss,
+                               accumulate, ev);
+    const float *W1 = (const float *)W1v, *W2 = (const float *)W2v, *X = (const float *)Xv;
 
     const MlpLayout L = mlp_layout(d, batch);
     if (!d->workspace || ((uintptr_t)d->workspace & 255) || d->workspace_bytes < L.bytes)
@@ -448,6 +547,144 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const float *W1, const float *W2, con
     return ULSNN_OK;
 }
 
+// The same gradient with X, W1, W2 stored as bf16 (operand_dtype 1): H, dO and dA1 are kept in bf16 and fed to
+// the bf16 matrix instructions, every product accumulates in fp32, logits, softmax, loss and the weight gradients
+// stay fp32.
+int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const u16 *X, const int32_t *labels,
+                    int batch, float *dW1, float *dW2, float *loss, bool accumulate, hipEvent_t *ev)
+{
+    hipStream_t s = (hipStream_t)d->hip_stream;
+    const int n_in = d->n_in, n_hid = d->n_hid, n_out = d->n_out;
+    const bool biases = d->b1 != nullptr;
+    const MlpLayout L = mlp_layout(d, batch);
+    if (!d->workspace || ((uintptr_t)d->workspace & 255) || d->workspace_bytes < L.bytes)
+        return ULSNN_ERR_WORKSPACE;
+    char *ws = (char *)d->workspace;
+    u16 *H = (u16 *)(ws + L.off_h);
+    float *Z = (float *)(ws + L.off_z);
+    u16 *dO = (u16 *)(ws + L.off_do16);
+    u16 *dA1 = (u16 *)(ws + L.off_da1);
+    float *row_loss = (float *)(ws + L.off_rowloss);
+    float *part_a = (float *)(ws + L.off_pa);
+    float *part_b = (float *)(ws + L.off_pb);
+
+    // weights whose rows are not 16-byte aligned (n_out = 3203) are copied once into aligned rows
+    int ldw1 = n_hid, ldw2 = n_out;
+    if (!rows_16b_aligned(W1, ldw1)) {
+        u16 *W1p = (u16 *)(ws + L.off_w1p);
+        hipLaunchKernelGGL(repack16_kernel, dim3(grid_for((size_t)n_in * n_hid)), dim3(256), 0, s, W1, ldw1, W1p,
+                           L.ldw1p, n_in, n_hid);
+        W1 = W1p;
+        ldw1 = L.ldw1p;
+    }
+    if (!rows_16b_aligned(W2, ldw2)) {
+        u16 *W2p = (u16 *)(ws + L.off_w2p);
+        hipLaunchKernelGGL(repack16_kernel, dim3(grid_for((size_t)n_hid * n_out)), dim3(256), 0, s, W2, ldw2, W2p,
+                           L.ldw2p, n_hid, n_out);
+        W2 = W2p;
+        ldw2 = L.ldw2p;
+    }
+    HIP_TRY(hipGetLastError());
+
+    for (int r0 = 0; r0 < batch; r0 += L.slab) {
+        const int rows = std::min(L.slab, batch - r0);
+        const float beta = (r0 > 0 || accumulate) ? 1.0f : 0.0f;
+        const u16 *Xs = X + (size_t)r0 * n_in;
+        const int32_t *ys = labels + r0;
+        const Gemm16Plan p1 = plan_gemm16(rows, n_hid, n_in, true, false, false, 0);
+        const Gemm16Plan p2 = plan_gemm16(rows, n_out, n_hid, true, false, false, 0);
+        const Gemm16Plan p3 = plan_gemm16(n_hid, n_out, rows, false, false, true, L.floats_pa);
+        const Gemm16Plan p4 = plan_gemm16(rows, n_hid, n_out, true, true, true, L.floats_pb);
+        const Gemm16Plan p5 = plan_gemm16(n_in, n_hid, rows, false, false, true, L.floats_pa);
+        Gemm16Args a{};
+        MARK(0);
+
+        // H = tanh(Xs W1 + b1), stored bf16
+        a = Gemm16Args{};
+        a.A = Xs; a.lda = n_in; a.B = W1; a.ldb = ldw1; a.C = H; a.ldc = L.ldh;
+        a.M = rows; a.N = n_hid; a.K = n_in; a.alpha = 1.f; a.bias = d->b1;
+        HIP_TRY(launch_gemm16(p1, true, false, EPI_BIAS_TANH, a, s));
+        MARK(1);
+
+        // Z = H W2 + b2, fp32
+        a = Gemm16Args{};
+        a.A = H; a.lda = L.ldh; a.B = W2; a.ldb = ldw2; a.C = Z; a.ldc = L.ldz;
+        a.M = rows; a.N = n_out; a.K = n_hid; a.alpha = 1.f; a.bias = d->b2;
+        HIP_TRY(launch_gemm16(p2, true, false, EPI_BIAS, a, s));
+        MARK(2);
+
+        // dO = softmax(Z) - onehot in bf16; loss (+)= sum of the row losses
+        if (n_out <= 256 * 16) {
+            hipLaunchKernelGGL((softmax_ce_kernel<256, 16, true>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out, ys,
+                               row_loss, dO, L.ldz);
+        } else {
+            hipLaunchKernelGGL((softmax_ce_long_kernel<256, true>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out, ys,
+                               row_loss, dO, L.ldz);
+        }
+        hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, row_loss, (long long)rows, loss, beta);
+        HIP_TRY(hipGetLastError());
+        MARK(3);
+
+        // dA1 = (dO W2^T) * (1 - H*H), stored bf16
+        Gemm16Args a4{};
+        a4.A = dO; a4.lda = L.ldz; a4.B = W2; a4.ldb = ldw2; a4.C = dA1; a4.ldc = L.ldh;
+        a4.M = rows; a4.N = n_hid; a4.K = n_out; a4.alpha = 1.f; a4.aux = H; a4.ldaux = L.ldh;
+        // dW2 (+)= H^T dO
+        Gemm16Args a3{};
+        a3.A = H; a3.lda = L.ldh; a3.B = dO; a3.ldb = L.ldz; a3.C = dW2; a3.ldc = n_out;
+        a3.M = n_hid; a3.N = n_out; a3.K = rows; a3.alpha = 1.f; a3.beta = beta;
+        {
+            Gemm16Args q4 = a4, q3 = a3;
+            if (p4.splits > 1) { q4.C = part_b; q4.partial_stride = (size_t)a4.M * a4.N; }
+            if (p3.splits > 1) { q3.C = part_a; q3.partial_stride = (size_t)a3.M * a3.N; }
+            HIP_TRY(launch_gemm16(p4, true, true, p4.splits > 1 ? EPI_PARTIAL : EPI_TANHGRAD, q4, s));
+            HIP_TRY(launch_gemm16(p3, false, false, p3.splits > 1 ? EPI_PARTIAL : EPI_AXPBY, q3, s));
+        }
+        MARK(4);
+        if (p4.splits > 1) {
+            const size_t total = (size_t)a4.M * a4.N;
+            hipLaunchKernelGGL((splitk_reduce_kernel<true, true>), dim3(grid_for(total)), dim3(256), 0, s, part_b, total,
+                               p4.splits, (void *)dA1, a4.M, a4.N, a4.ldc, 1.0f, 0.0f, (const void *)H, L.ldh);
+        }
+        if (p3.splits > 1) {
+            const size_t total = (size_t)a3.M * a3.N;
+            hipLaunchKernelGGL((splitk_reduce_kernel<false, false>), dim3(grid_for(total)), dim3(256), 0, s, part_a,
+                               total, p3.splits, (void *)dW2, a3.M, a3.N, a3.ldc, 1.0f, beta, (const void *)nullptr, 0);
+        }
+        HIP_TRY(hipGetLastError());
+        MARK(5);
+
+        // dW1 (+)= Xs^T dA1
+        a = Gemm16Args{};
+        a.A = Xs; a.lda = n_in; a.B = dA1; a.ldb = L.ldh; a.C = dW1; a.ldc = n_hid;
+        a.M = n_in; a.N = n_hid; a.K = rows; a.alpha = 1.f; a.beta = beta;
+        if (p5.splits > 1) {
+            Gemm16Args q5 = a;
+            q5.C = part_a; q5.partial_stride = (size_t)a.M * a.N;
+            HIP_TRY(launch_gemm16(p5, false, false, EPI_PARTIAL, q5, s));
+            MARK(6);
+            const size_t total = (size_t)a.M * a.N;
+            hipLaunchKernelGGL((splitk_reduce_kernel<false, false>), dim3(grid_for(total)), dim3(256), 0, s, part_a,
+                               total, p5.splits, (void *)dW1, a.M, a.N, a.ldc, 1.0f, beta, (const void *)nullptr, 0);
+            HIP_TRY(hipGetLastError());
+        } else {
+            HIP_TRY(launch_gemm16(p5, false, false, EPI_AXPBY, a, s));
+            MARK(6);
+        }
+        MARK(7);
+
+        if (biases) {
+            hipLaunchKernelGGL(column_sum16_kernel, dim3((n_out + 63) / 64), dim3(256), 0, s, dO, L.ldz, rows, n_out,
+                               d->db2, beta);
+            hipLaunchKernelGGL(column_sum16_kernel, dim3((n_hid + 63) / 64), dim3(256), 0, s, dA1, L.ldh, rows, n_hid,
+                               d->db1, beta);
+            HIP_TRY(hipGetLastError());
+        }
+        MARK(8);
+    }
+    return ULSNN_OK;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------------------
@@ -492,7 +729,7 @@ int ulsnn_mlp_grad(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, c
 {
     const int rc = check_mlp_args(desc, W1, W2, X, labels, batch, dW1, dW2, loss);
     if (rc != ULSNN_OK) return rc;
-    return mlp_grad_impl(desc, (const float *)W1, (const float *)W2, (const float *)X, labels, batch, dW1, dW2,
+    return mlp_grad_impl(desc, W1, W2, X, labels, batch, dW1, dW2,
                          loss, desc->accumulate != 0);
 }
 
@@ -504,16 +741,16 @@ int ulsnn_mlp_grad_epoch(const ulsnn_mlp_desc *desc, const void *W1, const void 
     if (rc != ULSNN_OK) return rc;
     if (chunk < 1) return ULSNN_ERR_DIM;
     if (n_patterns == 0)
-        return mlp_grad_impl(desc, (const float *)W1, (const float *)W2, nullptr, nullptr, 0, dW1, dW2, loss,
+        return mlp_grad_impl(desc, W1, W2, nullptr, nullptr, 0, dW1, dW2, loss,
                              desc->accumulate != 0);
     const int first = (int)std::min<int64_t>(chunk, n_patterns);
     if (!desc->workspace || ((uintptr_t)desc->workspace & 255) ||
         desc->workspace_bytes < ulsnn_mlp_grad_workspace_bytes(desc, first))
         return ULSNN_ERR_WORKSPACE;
-    const float *Xf = (const float *)X;
+    const size_t elem = desc->operand_dtype == 1 ? 2 : 4;
     for (int64_t p0 = 0; p0 < n_patterns; p0 += chunk) {
         const int rows = (int)std::min<int64_t>(chunk, n_patterns - p0);
-        const int r = mlp_grad_impl(desc, (const float *)W1, (const float *)W2, Xf + (size_t)p0 * desc->n_in,
+        const int r = mlp_grad_impl(desc, W1, W2, (const char *)X + (size_t)p0 * desc->n_in * elem,
                                     labels + p0, rows, dW1, dW2, loss, p0 > 0 || desc->accumulate != 0);
         if (r != ULSNN_OK) return r;
     }
@@ -532,7 +769,7 @@ int ulsnn_mlp_grad_timed(const ulsnn_mlp_desc *desc, const void *W1, const void 
     for (; made <= ULSNN_MLP_STAGES; ++made)
         if (hipEventCreate(&ev[made]) != hipSuccess) { out = ULSNN_ERR_HIP; break; }
     if (out == ULSNN_OK)
-        out = mlp_grad_impl(desc, (const float *)W1, (const float *)W2, (const float *)X, labels, batch, dW1, dW2,
+        out = mlp_grad_impl(desc, W1, W2, X, labels, batch, dW1, dW2,
                             loss, desc->accumulate != 0, ev);
     if (out == ULSNN_OK && hipEventSynchronize(ev[ULSNN_MLP_STAGES]) != hipSuccess) out = ULSNN_ERR_HIP;
     if (out == ULSNN_OK)

@@ -91,7 +91,8 @@ def test_mlp_grad_argument_errors():
         assert _grad(_desc(), **{missing: 0}) == E_NULL
     assert _grad(_desc(b1=0x1000)) == E_NULL                     # biases: all four or none
     assert _grad(_desc(b1=0x1000, b2=0x1000, db1=0x1000)) == E_NULL
-    assert _grad(_desc(operand_dtype=1)) == E_UNSUP              # bf16 storage is reserved
+    assert _grad(_desc(operand_dtype=2)) == E_UNSUP              # only fp32 (0) and bf16 storage (1) exist
+    assert _grad(_desc(operand_dtype=1)) == E_WS                 # bf16 storage: accepted, then needs a workspace
     assert _grad(_desc(accumulate=2)) == E_UNSUP
     assert _grad(_desc()) == E_WS                                # no workspace
     need = ulsnn.mlp_grad_workspace_bytes(400, 480, 3203, 8)
@@ -112,6 +113,14 @@ def test_workspace_query():
     assert sizes[-1] == sizes[-2] == sizes[-3] == sizes[-4]      # constant above the internal pass size
     assert sizes[2] >= 4096 * (3203 + 2 * 480) * 4               # holds Z, H and dA1 of the batch
     assert sizes[-1] < 1 << 30                                   # and stays modest for any batch
+
+
+def test_bf16_workspace_is_separate_query():
+    w32 = ulsnn.mlp_grad_workspace_bytes(400, 480, 3203, 4096, 0)
+    w16 = ulsnn.mlp_grad_workspace_bytes(400, 480, 3203, 4096, 1)
+    assert w16 > 0 and w16 != w32
+    # bf16 path: H and dA1 take half the room, dO is kept beside the fp32 logits, plus aligned weight copies
+    assert w16 >= 4096 * (3232 * 4 + 3232 * 2 + 2 * 480 * 2) + 480 * 3208 * 2
 
 
 def test_plan_description():
