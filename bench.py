@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-sgemm", action="store_true", help="skip the standalone SGEMM sweep")
     ap.add_argument("--sgemm-sizes", type=int, nargs="*", default=[256, 1024, 4096, 8192])
+    ap.add_argument("--no-bf16", action="store_true", help="skip the bf16-operand workload (batch 65536)")
+    ap.add_argument("--no-large-batch", action="store_true", help="skip the fp32 batch-262144 chunk measurement")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (reference for HBM byte counters)")
     return ap.parse_args()
@@ -161,6 +163,42 @@ def main():
         "frac_of_fp32_mfma_peak": round(gflops / (PEAK_FP32_MFMA_TFLOPS * 1e3), 4),
         "loss": loss, "stages": stages, "roofline": roofline,
     }
+    def time_batch(W1_, W2_, X_, y_, reps):
+        b = X_.shape[0]
+        odt = 1 if W1_.dtype == torch.bfloat16 else 0
+        ws_ = torch.empty(ulsnn.mlp_grad_workspace_bytes(shape.n_in, shape.n_hid, shape.n_out, b, odt),
+                          dtype=torch.uint8, device=dev)
+        out_ = ulsnn.MlpGradResult(torch.empty(W1_.shape, device=dev), torch.empty(W2_.shape, device=dev),
+                                   torch.empty(1, device=dev))
+        for _ in range(2):
+            ulsnn.mlp_grad(W1_, W2_, X_, y_, out=out_, workspace=ws_)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(reps):
+            ulsnn.mlp_grad(W1_, W2_, X_, y_, out=out_, workspace=ws_)
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t1) / reps
+        fl = ulsnn.mlp_grad_flops(shape.n_in, shape.n_hid, shape.n_out, b)
+        return {"batch": b, "ms": round(sec * 1e3, 4), "gflops": round(fl / sec / 1e9, 1),
+                "patterns_per_s": round(b / sec, 1)}
+
+    if not args.no_large_batch:
+        # one chunk of the epoch workload (BASELINE configs[3]): 262144 patterns resident in HBM, fp32
+        Xl, yl = si.mlp_patterns(shape, SEED, 0, 262144, device=dev)
+        r = time_batch(W1, W2, Xl, yl, 3)
+        r["frac_of_fp32_mfma_peak"] = round(r["gflops"] / (PEAK_FP32_MFMA_TFLOPS * 1e3), 4)
+        r["workload"] = "same net, fp32, one 262144-pattern chunk of the 9,000,000-pattern epoch"
+        result["large_batch"] = r
+        del Xl, yl
+    if not args.no_bf16:
+        # bf16-operand workload (BASELINE configs[4]): X, W stored bf16, batch 65536, fp32 accumulation
+        Xb, yb = si.mlp_patterns(shape, SEED, 0, 65536, device=dev)
+        r = time_batch(W1.to(torch.bfloat16), W2.to(torch.bfloat16), Xb.to(torch.bfloat16), yb, 5)
+        r["x_of_fp32_mfma_peak"] = round(r["gflops"] / (PEAK_FP32_MFMA_TFLOPS * 1e3), 3)
+        r["frac_of_bf16_mfma_peak"] = round(r["gflops"] / 2.5e6, 4)
+        r["workload"] = "same net, X/W/H/dO/dA1 in bf16, fp32 accumulate, batch 65536"
+        result["bf16"] = r
+        del Xb, yb
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)

@@ -34,6 +34,12 @@ def lib():
             f = getattr(L, "ref_mlp_loss_" + name)
             f.argtypes = [C.c_int] * 4 + [rp] * 5 + [ip, dp]
             f.restype = C.c_int
+            g = getattr(L, "ref_mlp_grad_mse_" + name)
+            g.argtypes = [C.c_int] * 4 + [rp] * 6 + [rp] * 4 + [dp] + [rp] * 2
+            g.restype = C.c_int
+            f = getattr(L, "ref_mlp_mse_" + name)
+            f.argtypes = [C.c_int] * 4 + [rp] * 6 + [dp]
+            f.restype = C.c_int
         L.ref_sgemm.restype = L.ref_sgemm_exact.restype = L.ref_threads.restype = C.c_int
         _lib = L
     return _lib
@@ -134,6 +140,54 @@ def mlp_loss(W1, W2, X, labels, b1=None, b2=None, dtype=np.float64) -> float:
                                                C.byref(loss))
     if rc:
         raise ValueError(f"ref_mlp_loss: error {rc}")
+    return loss.value
+
+
+class MlpMseGrad:
+    """Result of one oracle evaluation of the paper's tanh-output / squared-error form."""
+    __slots__ = ("dW1", "dW2", "db1", "db2", "loss", "H", "Y")
+
+
+def mlp_grad_mse(W1, W2, X, T, b1=None, b2=None, dtype=np.float64, intermediates: bool = False) -> MlpMseGrad:
+    """E = sum (tanh(tanh(X W1 + b1) W2 + b2) - T)^2 and its true gradient, every operation in `dtype`."""
+    dtype = np.dtype(dtype)
+    ct, sfx = (C.c_double, "f64") if dtype == np.float64 else (C.c_float, "f32")
+    cv = lambda a: None if a is None else np.ascontiguousarray(np.asarray(a), dtype=dtype)
+    W1, W2, X, T, b1, b2 = cv(W1), cv(W2), cv(X), cv(T), cv(b1), cv(b2)
+    n_in, n_hid = W1.shape
+    n_out = W2.shape[1]
+    batch = X.shape[0]
+    assert W2.shape[0] == n_hid and X.shape == (batch, n_in) and T.shape == (batch, n_out)
+    assert (b1 is None) == (b2 is None)
+    r = MlpMseGrad()
+    r.dW1 = np.empty((n_in, n_hid), dtype)
+    r.dW2 = np.empty((n_hid, n_out), dtype)
+    r.db1 = None if b1 is None else np.empty(n_hid, dtype)
+    r.db2 = None if b2 is None else np.empty(n_out, dtype)
+    r.H = np.empty((batch, n_hid), dtype) if intermediates else None
+    r.Y = np.empty((batch, n_out), dtype) if intermediates else None
+    loss = C.c_double(0.0)
+    rc = getattr(lib(), "ref_mlp_grad_mse_" + sfx)(
+        n_in, n_hid, n_out, batch, _p(W1, ct), _p(W2, ct), _p(b1, ct), _p(b2, ct), _p(X, ct), _p(T, ct),
+        _p(r.dW1, ct), _p(r.dW2, ct), _p(r.db1, ct), _p(r.db2, ct), C.byref(loss), _p(r.H, ct), _p(r.Y, ct))
+    if rc:
+        raise ValueError(f"ref_mlp_grad_mse: error {rc}")
+    r.loss = loss.value
+    return r
+
+
+def mlp_mse(W1, W2, X, T, b1=None, b2=None, dtype=np.float64) -> float:
+    """E alone (forward only)."""
+    dtype = np.dtype(dtype)
+    ct, sfx = (C.c_double, "f64") if dtype == np.float64 else (C.c_float, "f32")
+    cv = lambda a: None if a is None else np.ascontiguousarray(np.asarray(a), dtype=dtype)
+    W1, W2, X, T, b1, b2 = cv(W1), cv(W2), cv(X), cv(T), cv(b1), cv(b2)
+    loss = C.c_double(0.0)
+    rc = getattr(lib(), "ref_mlp_mse_" + sfx)(W1.shape[0], W1.shape[1], W2.shape[1], X.shape[0], _p(W1, ct),
+                                              _p(W2, ct), _p(b1, ct), _p(b2, ct), _p(X, ct), _p(T, ct),
+                                              C.byref(loss))
+    if rc:
+        raise ValueError(f"ref_mlp_mse: error {rc}")
     return loss.value
 
 

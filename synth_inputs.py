@@ -23,7 +23,7 @@ from dataclasses import dataclass
 import torch
 
 # tensor ids (the `t` of the counter)
-T_X, T_W1, T_W2, T_B1, T_B2, T_LABELS, T_A, T_B, T_C = range(1, 10)
+T_X, T_W1, T_W2, T_B1, T_B2, T_LABELS, T_A, T_B, T_C, T_TARGETS = range(1, 11)
 
 _MASK63 = 0x7FFFFFFFFFFFFFFF
 
@@ -146,6 +146,16 @@ def mlp_patterns(shape: MlpShape, seed: int, first: int, count: int, device="cpu
     X = normal(seed, T_X, count * shape.n_in, 1.0, start=first * shape.n_in, device=device)
     labels = integers(seed, T_LABELS, count, 0, shape.n_out, start=first, device=device)
     return X.reshape(count, shape.n_in), labels
+
+
+def mlp_targets(shape: MlpShape, seed: int, first: int, count: int, device="cpu"):
+    """Dense target matrix T[count x n_out] for the squared-error form: +0.9 for the pattern's class, -0.9
+    elsewhere (targets inside the range of tanh), plus uniform(-0.05, 0.05) noise so no two columns coincide."""
+    _, labels = mlp_patterns(shape, seed, first, count, device=device)
+    T = uniform(seed, T_TARGETS, count * shape.n_out, -0.05, 0.05, start=first * shape.n_out, device=device)
+    T = T.reshape(count, shape.n_out) - 0.9
+    T[torch.arange(count, device=device), labels.long()] += 1.8
+    return T
 
 
 def random_biases(shape: MlpShape, seed: int, std: float = 0.1, device="cpu"):
