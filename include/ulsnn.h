@@ -123,6 +123,34 @@ int ulsnn_mlp_grad(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, c
                    const int32_t *labels, int batch, float *dW1, float *dW2, float *loss);
 
 /*
+ * Error-only evaluation (forward pass and loss, no gradient): what a line search calls between gradients.
+ * Same network, operands, labels, workspace, accumulate and error rules as ulsnn_mlp_grad; only `loss` is
+ * written ((+)= with accumulate).  db1 / db2 of the descriptor are ignored.
+ * Counts 2 * batch * (n_in + n_out) * n_hid floating-point operations (section 6.2).
+ */
+int ulsnn_mlp_loss(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X,
+                   const int32_t *labels, int batch, float *loss);
+
+/*
+ * The paper's own output stage (sections 4.1, 4.2): tanh outputs and a summed squared error against a dense
+ * target matrix T [batch x n_out, dense row-major, device fp32]:
+ *
+ *     Y = tanh(H W2 + 1 b2^T)                       eq. (nn)
+ *     E = sum_r sum_c (Y[r][c] - T[r][c])^2         eq. (error): no 1/2, no 1/n; written to `loss`
+ *     dZ = 2 (Y - T) ** (1 - Y ** Y),  dW2 = H^T dZ,  dA1 = (dZ W2^T) ** (1 - H ** H),  dW1 = X^T dA1
+ *
+ * dW1 and dW2 are the TRUE derivatives of E.  In the paper's notation (Y_Delta = (1 - Y**Y)**(T - Y),
+ * grad_ho = Y_Delta^T * H, grad_ih = H_Delta^T * X, W_ho = W2^T, W_ih = W1^T): dW2 = -2 grad_ho^T and
+ * dW1 = -2 grad_ih^T; the paper's "gradient" is an ascent direction of -E/2.
+ * fp32 operands only (operand_dtype 1 returns ULSNN_ERR_UNSUPPORTED); everything else as ulsnn_mlp_grad.
+ * ulsnn_mlp_mse is the error-only form (E alone).
+ */
+int ulsnn_mlp_grad_mse(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X, const float *T,
+                       int batch, float *dW1, float *dW2, float *loss);
+int ulsnn_mlp_mse(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X, const float *T,
+                  int batch, float *loss);
+
+/*
  * Gradient over a whole training set held in device memory, taken `chunk` patterns at a time and summed
  * (section 4.3: additive over patterns; section 6.2: each processor steps through its patterns a fixed
  * number at a time).  Equivalent to ulsnn_mlp_grad on patterns [0, chunk), then with accumulate = 1 on
@@ -160,6 +188,8 @@ int ulsnn_mlp_grad_describe_plan(const ulsnn_mlp_desc *desc, int batch, char *bu
 /* Counting conventions (host-only): 2mnk (section 3.1) and batch*(4 n_in n_hid + 6 n_hid n_out) (section 6.2). */
 double ulsnn_sgemm_flops(int m, int n, int k);
 double ulsnn_mlp_grad_flops(int n_in, int n_hid, int n_out, int64_t batch);
+/* 2 * batch * (n_in + n_out) * n_hid for one evaluation of the error alone (section 6.2). */
+double ulsnn_mlp_loss_flops(int n_in, int n_hid, int n_out, int64_t batch);
 
 /* Human-readable name of a status code (static storage; never NULL). */
 const char *ulsnn_status_string(int status);

@@ -12,6 +12,10 @@ from .binding import (  # noqa: F401
     mlp_grad_describe_plan,
     mlp_grad_epoch,
     mlp_grad_flops,
+    mlp_grad_mse,
+    mlp_loss,
+    mlp_loss_flops,
+    mlp_mse,
     mlp_grad_timed,
     MLP_STAGES,
     mlp_grad_workspace_bytes,

@@ -55,6 +55,14 @@ def load():
     L.ulsnn_mlp_grad_epoch.restype = i
     L.ulsnn_mlp_grad_timed.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, i, vp, vp, vp, C.POINTER(C.c_float)]
     L.ulsnn_mlp_grad_timed.restype = i
+    L.ulsnn_mlp_loss.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, i, vp]
+    L.ulsnn_mlp_loss.restype = i
+    L.ulsnn_mlp_grad_mse.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, i, vp, vp, vp]
+    L.ulsnn_mlp_grad_mse.restype = i
+    L.ulsnn_mlp_mse.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, i, vp]
+    L.ulsnn_mlp_mse.restype = i
+    L.ulsnn_mlp_loss_flops.argtypes = [i, i, i, C.c_int64]
+    L.ulsnn_mlp_loss_flops.restype = C.c_double
     L.ulsnn_mlp_grad_describe_plan.argtypes = [C.POINTER(_MlpDesc), i, C.c_char_p, C.c_size_t]
     L.ulsnn_mlp_grad_describe_plan.restype = i
     L.ulsnn_sgemm_flops.argtypes = [i, i, i]
@@ -83,6 +91,10 @@ def sgemm_flops(m: int, n: int, k: int) -> float:
 
 def mlp_grad_flops(n_in: int, n_hid: int, n_out: int, batch: int) -> float:
     return float(load().ulsnn_mlp_grad_flops(n_in, n_hid, n_out, batch))
+
+
+def mlp_loss_flops(n_in: int, n_hid: int, n_out: int, batch: int) -> float:
+    return float(load().ulsnn_mlp_loss_flops(n_in, n_hid, n_out, batch))
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -152,9 +164,10 @@ class MlpGradResult:
     db2: Optional[torch.Tensor] = None
 
 
-def _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate):
+def _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate, dense_targets=False):
     """Checks shapes and types; returns (n_in, n_hid, n_out, out, operand_dtype).  W1, W2 and X are all float32
-    (operand_dtype 0) or all bfloat16 (operand_dtype 1); gradients and loss are always float32."""
+    (operand_dtype 0) or all bfloat16 (operand_dtype 1); gradients and loss are always float32.  `labels` is the
+    int32 label vector, or with dense_targets the float32 target matrix [batch x n_out]."""
     if W1.dtype == torch.bfloat16:
         for t, nm in ((W1, "W1"), (W2, "W2"), (X, "X")):
             if not (t.is_cuda and t.dtype == torch.bfloat16):
@@ -163,7 +176,11 @@ def _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate):
     else:
         _dev_f32(W1, "W1"), _dev_f32(W2, "W2"), _dev_f32(X, "X")
         operand_dtype = 0
-    if not (labels.is_cuda and labels.dtype == torch.int32):
+    if dense_targets:
+        _dev_f32(labels, "T")
+        if labels.dim() != 2 or labels.shape[1] != W2.shape[1]:
+            raise ValueError("T must be [batch x n_out]")
+    elif not (labels.is_cuda and labels.dtype == torch.int32):
         raise TypeError("labels must be an int32 tensor on the GPU")
     for t in (W1, W2, X, labels):
         if not t.is_contiguous():
@@ -198,6 +215,50 @@ def mlp_grad(W1, W2, X, labels, b1=None, b2=None, *, out: Optional[MlpGradResult
                                _ptr(out.dW2), _ptr(out.loss))
     if rc:
         raise UlsnnError(rc, "ulsnn_mlp_grad")
+    return out
+
+
+def _loss_only(entry, W1, W2, X, targets, b1, b2, loss, accumulate, workspace, stream, dense):
+    n_in, n_hid, n_out, _, odt = _mlp_common(W1, W2, X, targets, b1, b2, MlpGradResult(None, None, None), accumulate,
+                                              dense_targets=dense)
+    batch = X.shape[0]
+    if loss is None:
+        if accumulate:
+            raise ValueError("accumulate=True needs the tensor to add to (loss=...)")
+        loss = torch.empty(1, device=W1.device)
+    if workspace is None:
+        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch, odt)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
+    d = _desc(n_in, n_hid, n_out, b1, b2, None, None, accumulate, workspace, stream, odt)
+    rc = getattr(load(), entry)(C.byref(d), _ptr(W1), _ptr(W2), _ptr(X), _ptr(targets), batch, _ptr(loss))
+    if rc:
+        raise UlsnnError(rc, entry)
+    return loss
+
+
+def mlp_loss(W1, W2, X, labels, b1=None, b2=None, *, loss=None, accumulate=False, workspace=None, stream=None):
+    """Loss alone, summed over the rows of X (ulsnn_mlp_loss).  Returns the one-element device tensor."""
+    return _loss_only("ulsnn_mlp_loss", W1, W2, X, labels, b1, b2, loss, accumulate, workspace, stream, False)
+
+
+def mlp_mse(W1, W2, X, T, b1=None, b2=None, *, loss=None, accumulate=False, workspace=None, stream=None):
+    """Summed squared error of the tanh-output network against dense targets T (ulsnn_mlp_mse)."""
+    return _loss_only("ulsnn_mlp_mse", W1, W2, X, T, b1, b2, loss, accumulate, workspace, stream, True)
+
+
+def mlp_grad_mse(W1, W2, X, T, b1=None, b2=None, *, out: Optional[MlpGradResult] = None, accumulate=False,
+                 workspace: Optional[torch.Tensor] = None, stream=None) -> MlpGradResult:
+    """Squared error of the tanh-output network and its gradient (ulsnn_mlp_grad_mse), the paper's own form."""
+    n_in, n_hid, n_out, out, odt = _mlp_common(W1, W2, X, T, b1, b2, out, accumulate, dense_targets=True)
+    batch = X.shape[0]
+    if workspace is None:
+        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch, odt)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
+    d = _desc(n_in, n_hid, n_out, b1, b2, out.db1, out.db2, accumulate, workspace, stream, odt)
+    rc = load().ulsnn_mlp_grad_mse(C.byref(d), _ptr(W1), _ptr(W2), _ptr(X), _ptr(T), batch, _ptr(out.dW1),
+                                   _ptr(out.dW2), _ptr(out.loss))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_mlp_grad_mse")
     return out
 
 

@@ -58,7 +58,8 @@ __device__ __forceinline__ float block_sum(float v, float *red)
 //     row_loss[r] = m + ln s - z_label     (0 if the label is out of range)
 // The row is read from HBM once into registers (PER values per thread), so Z is read once and written once.
 // With OUT_BF16 the delta is written, rounded to bf16, to `out16` (row stride ld16) and Z is left untouched.
-template <int THREADS, int PER, bool OUT_BF16 = false>
+// With WRITE_DELTA = false only the row loss is produced (error-only evaluation): Z is read and nothing else written.
+template <int THREADS, int PER, bool OUT_BF16 = false, bool WRITE_DELTA = true>
 __global__ __launch_bounds__(THREADS) void softmax_ce_kernel(float *__restrict__ Z, int ldz, int n,
                                                              const int32_t *__restrict__ labels,
                                                              float *__restrict__ row_loss,
@@ -88,6 +89,7 @@ __global__ __launch_bounds__(THREADS) void softmax_ce_kernel(float *__restrict__
     s = block_sum<THREADS>(s, red);
     const float inv = 1.0f / s;
     if (threadIdx.x == 0) row_loss[r] = labelled ? (m + __logf(s)) - z[y] : 0.f;
+    if (!WRITE_DELTA) return;
     __syncthreads();                       // z[y] is read before any thread overwrites it
 #pragma unroll
     for (int e = 0; e < PER; ++e) {
@@ -101,7 +103,7 @@ __global__ __launch_bounds__(THREADS) void softmax_ce_kernel(float *__restrict__
 }
 
 // Same operation for rows too long for registers: three passes over the row (the re-reads hit in cache).
-template <int THREADS, bool OUT_BF16 = false>
+template <int THREADS, bool OUT_BF16 = false, bool WRITE_DELTA = true>
 __global__ __launch_bounds__(THREADS) void softmax_ce_long_kernel(float *__restrict__ Z, int ldz, int n,
                                                                   const int32_t *__restrict__ labels,
                                                                   float *__restrict__ row_loss,
@@ -120,12 +122,36 @@ __global__ __launch_bounds__(THREADS) void softmax_ce_long_kernel(float *__restr
     s = block_sum<THREADS>(s, red);
     const float inv = 1.0f / s;
     if (threadIdx.x == 0) row_loss[r] = labelled ? (m + __logf(s)) - z[y] : 0.f;
+    if (!WRITE_DELTA) return;
     __syncthreads();
     for (int c = threadIdx.x; c < n; c += THREADS) {
         const float d = labelled ? __expf(z[c] - m) * inv - (c == y ? 1.0f : 0.0f) : 0.0f;
         if (OUT_BF16) out16[(size_t)r * ld16 + c] = f32_to_bf16(d);
         else z[c] = d;
     }
+}
+
+// Output stage of the paper's own form (tanh outputs, summed squared error against dense targets): one workgroup
+// per pattern; Y holds the outputs y = tanh(z) (written by the output-layer product's epilogue).
+//     row_loss[r] = sum_c (y_c - t_c)^2,   y_c <- 2 (y_c - t_c) (1 - y_c^2)   (in place, if WRITE_DELTA)
+template <int THREADS, bool WRITE_DELTA>
+__global__ __launch_bounds__(THREADS) void mse_delta_kernel(float *__restrict__ Y, int ldy, int n,
+                                                            const float *__restrict__ T, int ldt,
+                                                            float *__restrict__ row_loss)
+{
+    __shared__ float red[THREADS / 64];
+    const int r = blockIdx.x;
+    float *y = Y + (size_t)r * ldy;
+    const float *t = T + (size_t)r * ldt;
+    float e = 0.f;
+    for (int c = threadIdx.x; c < n; c += THREADS) {
+        const float yv = y[c];
+        const float diff = yv - t[c];
+        e += diff * diff;
+        if (WRITE_DELTA) y[c] = 2.0f * diff * (1.0f - yv * yv);
+    }
+    e = block_sum<THREADS>(e, red);
+    if (threadIdx.x == 0) row_loss[r] = e;
 }
 
 // out = alpha * sum_z partial[z] + beta * out over an M x N matrix (partials dense, ld = N; out with ldc).

@@ -389,15 +389,16 @@ SlabPlans plan_slab(const MlpLayout &L, int n_in, int n_hid, int n_out, int rows
     return s;
 }
 
-int check_mlp_args(const ulsnn_mlp_desc *d, const void *W1, const void *W2, const void *X, const int32_t *labels,
-                   long long batch, float *dW1, float *dW2, float *loss)
+int check_mlp_args(const ulsnn_mlp_desc *d, const void *W1, const void *W2, const void *X, const void *targets,
+                   long long batch, const float *dW1, const float *dW2, const float *loss, bool backward)
 {
     if (!d) return ULSNN_ERR_NULL;
     if (d->n_in < 1 || d->n_hid < 1 || d->n_out < 1 || batch < 0) return ULSNN_ERR_DIM;
-    if (!W1 || !W2 || !dW1 || !dW2 || !loss) return ULSNN_ERR_NULL;
-    if (batch > 0 && (!X || !labels)) return ULSNN_ERR_NULL;
+    if (!W1 || !W2 || !loss) return ULSNN_ERR_NULL;
+    if (backward && (!dW1 || !dW2)) return ULSNN_ERR_NULL;
+    if (batch > 0 && (!X || !targets)) return ULSNN_ERR_NULL;
     const int nb = (d->b1 != nullptr) + (d->b2 != nullptr) + (d->db1 != nullptr) + (d->db2 != nullptr);
-    if (nb != 0 && nb != 4) return ULSNN_ERR_NULL;
+    if (backward ? (nb != 0 && nb != 4) : ((d->b1 != nullptr) != (d->b2 != nullptr))) return ULSNN_ERR_NULL;
     if (d->accumulate != 0 && d->accumulate != 1) return ULSNN_ERR_UNSUPPORTED;
     if (d->operand_dtype != 0 && d->operand_dtype != 1) return ULSNN_ERR_UNSUPPORTED;
     return ULSNN_OK;
@@ -413,12 +414,19 @@ int check_mlp_args(const ulsnn_mlp_desc *d, const void *W1, const void *W2, cons
     } while (0)
 
 // `ev`, if not null, is an array of ULSNN_MLP_STAGES + 1 events recorded at the stage boundaries.
-int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const u16 *X, const int32_t *labels,
+// What one call computes beyond the forward pass.
+struct MlpTask {
+    const int32_t *labels;   // softmax / cross-entropy output stage (targets == nullptr)
+    const float *targets;    // tanh / squared-error output stage of the paper: dense T[batch x n_out]
+    bool backward;           // false: loss only (error evaluation), dW1 / dW2 untouched
+};
+
+int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const u16 *X, const MlpTask &task,
                     int batch, float *dW1, float *dW2, float *loss, bool accumulate, hipEvent_t *ev);
 
 // W1v, W2v, Xv point at fp32 (operand_dtype 0) or bf16 (operand_dtype 1) data.
 int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, const void *Xv,
-                  const int32_t *labels, int batch, float *dW1, float *dW2, float *loss, bool accumulate,
+                  const MlpTask &task, int batch, float *dW1, float *dW2, float *loss, bool accumulate,
                   hipEvent_t *ev = nullptr)
 {
     hipStream_t s = (hipStream_t)d->hip_stream;
@@ -427,12 +435,14 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, con
 
     if (batch == 0) {
         if (!accumulate) {
-            hipLaunchKernelGGL(zero_kernel, dim3(grid_for((size_t)n_in * n_hid)), dim3(256), 0, s, dW1,
-                               (size_t)n_in * n_hid);
-            hipLaunchKernelGGL(zero_kernel, dim3(grid_for((size_t)n_hid * n_out)), dim3(256), 0, s, dW2,
-                               (size_t)n_hid * n_out);
             hipLaunchKernelGGL(zero_kernel, dim3(1), dim3(256), 0, s, loss, (size_t)1);
-            if (biases) {
+            if (task.backward) {
+                hipLaunchKernelGGL(zero_kernel, dim3(grid_for((size_t)n_in * n_hid)), dim3(256), 0, s, dW1,
+                                   (size_t)n_in * n_hid);
+                hipLaunchKernelGGL(zero_kernel, dim3(grid_for((size_t)n_hid * n_out)), dim3(256), 0, s, dW2,
+                                   (size_t)n_hid * n_out);
+            }
+            if (biases && task.backward) {
                 hipLaunchKernelGGL(zero_kernel, dim3(grid_for(n_hid)), dim3(256), 0, s, d->db1, (size_t)n_hid);
                 hipLaunchKernelGGL(zero_kernel, dim3(grid_for(n_out)), dim3(256), 0, s, d->db2, (size_t)n_out);
             }
@@ -442,7 +452,7 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, con
     }
 
     if (d->operand_dtype == 1)
-        return mlp_grad_impl16(d, (const u16 *)W1v, (const u16 *)W2v, (const u16 *)Xv, labels, batch, dW1, dW2, loss,
+        return mlp_grad_impl16(d, (const u16 *)W1v, (const u16 *)W2v, (const u16 *)Xv, task, batch, dW1, dW2, loss,
                                accumulate, ev);
     const float *W1 = (const float *)W1v, *W2 = (const float *)W2v, *X = (const float *)Xv;
 
@@ -462,7 +472,8 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, con
         const SlabPlans P = plan_slab(L, n_in, n_hid, n_out, rows);
         const float beta = (r0 > 0 || accumulate) ? 1.0f : 0.0f;
         const float *Xs = X + (size_t)r0 * n_in;
-        const int32_t *ys = labels + r0;
+        const int32_t *ys = task.labels ? task.labels + r0 : nullptr;
+        const float *ts = task.targets ? task.targets + (size_t)r0 * n_out : nullptr;
         GemmArgs a{};
         MARK(0);
 
@@ -473,24 +484,43 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, con
         HIP_TRY(launch_gemm(P.g1, true, false, EPI_BIAS_TANH, a, s));
         MARK(1);
 
-        // Z = H W2 + b2
+        // Z = H W2 + b2   (softmax form)   or   Y = tanh(H W2 + b2)   (the paper's form)
         a = GemmArgs{};
         a.A = H; a.lda = L.ldh; a.B = W2; a.ldb = n_out; a.C = Z; a.ldc = L.ldz;
         a.M = rows; a.N = n_out; a.K = n_hid; a.alpha = 1.f; a.beta = 0.f; a.bias = d->b2;
-        HIP_TRY(launch_gemm(P.g2, true, false, EPI_BIAS, a, s));
+        HIP_TRY(launch_gemm(P.g2, true, false, ts ? EPI_BIAS_TANH : EPI_BIAS, a, s));
         MARK(2);
 
-        // Z <- dO = softmax(Z) - onehot, row losses; loss (+)= their sum
-        if (n_out <= 256 * 16) {
-            hipLaunchKernelGGL((softmax_ce_kernel<256, 16>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out, ys,
-                               row_loss);
+        // output stage: row losses and, for a gradient, the output delta in place of Z; loss (+)= their sum
+        if (ts) {
+            if (task.backward)
+                hipLaunchKernelGGL((mse_delta_kernel<256, true>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out, ts,
+                                   n_out, row_loss);
+            else
+                hipLaunchKernelGGL((mse_delta_kernel<256, false>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out, ts,
+                                   n_out, row_loss);
+        } else if (n_out <= 256 * 16) {
+            if (task.backward)
+                hipLaunchKernelGGL((softmax_ce_kernel<256, 16>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out, ys,
+                                   row_loss, (u16 *)nullptr, 0);
+            else
+                hipLaunchKernelGGL((softmax_ce_kernel<256, 16, false, false>), dim3(rows), dim3(256), 0, s, Z, L.ldz,
+                                   n_out, ys, row_loss, (u16 *)nullptr, 0);
         } else {
-            hipLaunchKernelGGL((softmax_ce_long_kernel<256>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out, ys,
-                               row_loss);
+            if (task.backward)
+                hipLaunchKernelGGL((softmax_ce_long_kernel<256>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out, ys,
+                                   row_loss, (u16 *)nullptr, 0);
+            else
+                hipLaunchKernelGGL((softmax_ce_long_kernel<256, false, false>), dim3(rows), dim3(256), 0, s, Z, L.ldz,
+                                   n_out, ys, row_loss, (u16 *)nullptr, 0);
         }
         hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, row_loss, (long long)rows, loss, beta);
         HIP_TRY(hipGetLastError());
         MARK(3);
+        if (!task.backward) {
+            MARK(4); MARK(5); MARK(6); MARK(7); MARK(8);
+            continue;
+        }
 
         // dW2 (+)= H^T dO   and   dA1 = (dO W2^T) * (1 - H*H): independent of each other
         GemmArgs a3{}, a4{};
@@ -550,9 +580,10 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, con
 // The same gradient with X, W1, W2 stored as bf16 (operand_dtype 1): H, dO and dA1 are kept in bf16 and fed to
 // the bf16 matrix instructions, every product accumulates in fp32, logits, softmax, loss and the weight gradients
 // stay fp32.
-int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const u16 *X, const int32_t *labels,
+int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const u16 *X, const MlpTask &task,
                     int batch, float *dW1, float *dW2, float *loss, bool accumulate, hipEvent_t *ev)
 {
+    if (task.targets) return ULSNN_ERR_UNSUPPORTED;   // the squared-error form exists for fp32 operands only
     hipStream_t s = (hipStream_t)d->hip_stream;
     const int n_in = d->n_in, n_hid = d->n_hid, n_out = d->n_out;
     const bool biases = d->b1 != nullptr;
@@ -590,7 +621,7 @@ int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const
         const int rows = std::min(L.slab, batch - r0);
         const float beta = (r0 > 0 || accumulate) ? 1.0f : 0.0f;
         const u16 *Xs = X + (size_t)r0 * n_in;
-        const int32_t *ys = labels + r0;
+        const int32_t *ys = task.labels + r0;
         const Gemm16Plan p1 = plan_gemm16(rows, n_hid, n_in, true, false, false, 0);
         const Gemm16Plan p2 = plan_gemm16(rows, n_out, n_hid, true, false, false, 0);
         const Gemm16Plan p3 = plan_gemm16(n_hid, n_out, rows, false, false, true, L.floats_pa);
@@ -613,17 +644,29 @@ int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const
         HIP_TRY(launch_gemm16(p2, true, false, EPI_BIAS, a, s));
         MARK(2);
 
-        // dO = softmax(Z) - onehot in bf16; loss (+)= sum of the row losses
+        // dO = softmax(Z) - onehot in bf16 (for a gradient); loss (+)= sum of the row losses
         if (n_out <= 256 * 16) {
-            hipLaunchKernelGGL((softmax_ce_kernel<256, 16, true>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out, ys,
-                               row_loss, dO, L.ldz);
+            if (task.backward)
+                hipLaunchKernelGGL((softmax_ce_kernel<256, 16, true>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out, ys,
+                                   row_loss, dO, L.ldz);
+            else
+                hipLaunchKernelGGL((softmax_ce_kernel<256, 16, false, false>), dim3(rows), dim3(256), 0, s, Z, L.ldz,
+                                   n_out, ys, row_loss, (u16 *)nullptr, 0);
         } else {
-            hipLaunchKernelGGL((softmax_ce_long_kernel<256, true>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out, ys,
-                               row_loss, dO, L.ldz);
+            if (task.backward)
+                hipLaunchKernelGGL((softmax_ce_long_kernel<256, true>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out,
+                                   ys, row_loss, dO, L.ldz);
+            else
+                hipLaunchKernelGGL((softmax_ce_long_kernel<256, false, false>), dim3(rows), dim3(256), 0, s, Z, L.ldz,
+                                   n_out, ys, row_loss, (u16 *)nullptr, 0);
         }
         hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, row_loss, (long long)rows, loss, beta);
         HIP_TRY(hipGetLastError());
         MARK(3);
+        if (!task.backward) {
+            MARK(4); MARK(5); MARK(6); MARK(7); MARK(8);
+            continue;
+        }
 
         // dA1 = (dO W2^T) * (1 - H*H), stored bf16
         Gemm16Args a4{};
@@ -727,21 +770,49 @@ size_t ulsnn_mlp_grad_workspace_bytes(const ulsnn_mlp_desc *desc, int batch)
 int ulsnn_mlp_grad(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X,
                    const int32_t *labels, int batch, float *dW1, float *dW2, float *loss)
 {
-    const int rc = check_mlp_args(desc, W1, W2, X, labels, batch, dW1, dW2, loss);
+    const int rc = check_mlp_args(desc, W1, W2, X, labels, batch, dW1, dW2, loss, true);
     if (rc != ULSNN_OK) return rc;
-    return mlp_grad_impl(desc, W1, W2, X, labels, batch, dW1, dW2,
-                         loss, desc->accumulate != 0);
+    return mlp_grad_impl(desc, W1, W2, X, MlpTask{labels, nullptr, true}, batch, dW1, dW2, loss,
+                         desc->accumulate != 0);
+}
+
+int ulsnn_mlp_loss(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X,
+                   const int32_t *labels, int batch, float *loss)
+{
+    const int rc = check_mlp_args(desc, W1, W2, X, labels, batch, nullptr, nullptr, loss, false);
+    if (rc != ULSNN_OK) return rc;
+    return mlp_grad_impl(desc, W1, W2, X, MlpTask{labels, nullptr, false}, batch, nullptr, nullptr, loss,
+                         desc->accumulate != 0);
+}
+
+int ulsnn_mlp_grad_mse(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X, const float *T,
+                       int batch, float *dW1, float *dW2, float *loss)
+{
+    const int rc = check_mlp_args(desc, W1, W2, X, T, batch, dW1, dW2, loss, true);
+    if (rc != ULSNN_OK) return rc;
+    if (desc->operand_dtype != 0) return ULSNN_ERR_UNSUPPORTED;
+    return mlp_grad_impl(desc, W1, W2, X, MlpTask{nullptr, T, true}, batch, dW1, dW2, loss, desc->accumulate != 0);
+}
+
+int ulsnn_mlp_mse(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X, const float *T,
+                  int batch, float *loss)
+{
+    const int rc = check_mlp_args(desc, W1, W2, X, T, batch, nullptr, nullptr, loss, false);
+    if (rc != ULSNN_OK) return rc;
+    if (desc->operand_dtype != 0) return ULSNN_ERR_UNSUPPORTED;
+    return mlp_grad_impl(desc, W1, W2, X, MlpTask{nullptr, T, false}, batch, nullptr, nullptr, loss,
+                         desc->accumulate != 0);
 }
 
 int ulsnn_mlp_grad_epoch(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X,
                          const int32_t *labels, int64_t n_patterns, int chunk, float *dW1, float *dW2,
                          float *loss)
 {
-    const int rc = check_mlp_args(desc, W1, W2, X, labels, (long long)n_patterns, dW1, dW2, loss);
+    const int rc = check_mlp_args(desc, W1, W2, X, labels, (long long)n_patterns, dW1, dW2, loss, true);
     if (rc != ULSNN_OK) return rc;
     if (chunk < 1) return ULSNN_ERR_DIM;
     if (n_patterns == 0)
-        return mlp_grad_impl(desc, W1, W2, nullptr, nullptr, 0, dW1, dW2, loss,
+        return mlp_grad_impl(desc, W1, W2, nullptr, MlpTask{nullptr, nullptr, true}, 0, dW1, dW2, loss,
                              desc->accumulate != 0);
     const int first = (int)std::min<int64_t>(chunk, n_patterns);
     if (!desc->workspace || ((uintptr_t)desc->workspace & 255) ||
@@ -751,7 +822,8 @@ int ulsnn_mlp_grad_epoch(const ulsnn_mlp_desc *desc, const void *W1, const void 
     for (int64_t p0 = 0; p0 < n_patterns; p0 += chunk) {
         const int rows = (int)std::min<int64_t>(chunk, n_patterns - p0);
         const int r = mlp_grad_impl(desc, W1, W2, (const char *)X + (size_t)p0 * desc->n_in * elem,
-                                    labels + p0, rows, dW1, dW2, loss, p0 > 0 || desc->accumulate != 0);
+                                    MlpTask{labels + p0, nullptr, true}, rows, dW1, dW2, loss,
+                                    p0 > 0 || desc->accumulate != 0);
         if (r != ULSNN_OK) return r;
     }
     return ULSNN_OK;
@@ -760,7 +832,7 @@ int ulsnn_mlp_grad_epoch(const ulsnn_mlp_desc *desc, const void *W1, const void 
 int ulsnn_mlp_grad_timed(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X,
                          const int32_t *labels, int batch, float *dW1, float *dW2, float *loss, float *stage_ms)
 {
-    const int rc = check_mlp_args(desc, W1, W2, X, labels, batch, dW1, dW2, loss);
+    const int rc = check_mlp_args(desc, W1, W2, X, labels, batch, dW1, dW2, loss, true);
     if (rc != ULSNN_OK) return rc;
     if (!stage_ms) return ULSNN_ERR_NULL;
     if (batch < 1 || batch > SLAB_ROWS) return ULSNN_ERR_UNSUPPORTED;   // one internal pass only
@@ -769,8 +841,8 @@ int ulsnn_mlp_grad_timed(const ulsnn_mlp_desc *desc, const void *W1, const void 
     for (; made <= ULSNN_MLP_STAGES; ++made)
         if (hipEventCreate(&ev[made]) != hipSuccess) { out = ULSNN_ERR_HIP; break; }
     if (out == ULSNN_OK)
-        out = mlp_grad_impl(desc, W1, W2, X, labels, batch, dW1, dW2,
-                            loss, desc->accumulate != 0, ev);
+        out = mlp_grad_impl(desc, W1, W2, X, MlpTask{labels, nullptr, true}, batch, dW1, dW2, loss,
+                            desc->accumulate != 0, ev);
     if (out == ULSNN_OK && hipEventSynchronize(ev[ULSNN_MLP_STAGES]) != hipSuccess) out = ULSNN_ERR_HIP;
     if (out == ULSNN_OK)
         for (int i = 0; i < ULSNN_MLP_STAGES; ++i)
@@ -801,6 +873,11 @@ int ulsnn_mlp_grad_describe_plan(const ulsnn_mlp_desc *desc, int batch, char *bu
 }
 
 double ulsnn_sgemm_flops(int m, int n, int k) { return 2.0 * (double)m * (double)n * (double)k; }
+
+double ulsnn_mlp_loss_flops(int n_in, int n_hid, int n_out, int64_t batch)
+{
+    return 2.0 * (double)batch * ((double)n_in + n_out) * n_hid;
+}
 
 double ulsnn_mlp_grad_flops(int n_in, int n_hid, int n_out, int64_t batch)
 {

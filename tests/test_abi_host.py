@@ -39,6 +39,7 @@ def test_counting_conventions_match_the_paper():
     assert ulsnn.sgemm_flops(320, 320, 320) == 2 * 320**3
     assert ulsnn.mlp_grad_flops(400, 480, 3203, 1) == 9_992_640
     assert int(ulsnn.mlp_grad_flops(400, 480, 3203, 9_264_000) / 1e12) == 92
+    assert round(ulsnn.mlp_loss_flops(400, 480, 3203, 9_264_000) / 1e12) == 32      # "32 Tera" for one error evaluation
 
 
 def _sgemm(ta, tb, m, n, k, lda, ldb, ldc, A=1, B=1, Cm=1, alpha=1.0):
@@ -103,6 +104,21 @@ def test_mlp_grad_argument_errors():
     d = _desc(workspace=0x1000, workspace_bytes=1 << 40)
     assert L.ulsnn_mlp_grad_epoch(C.byref(d), p, p, p, p, 100, 0, p, p, p) == E_DIM
     assert L.ulsnn_mlp_grad_epoch(C.byref(_desc()), p, p, p, p, 100, 10, p, p, p) == E_WS
+
+
+def test_loss_only_and_mse_argument_errors():
+    L = ulsnn.load()
+    p, z = C.c_void_p(0x1000), C.c_void_p(0)
+    d = _desc()
+    assert L.ulsnn_mlp_loss(None, p, p, p, p, 8, p) == E_NULL
+    assert L.ulsnn_mlp_loss(C.byref(d), p, p, p, p, 8, z) == E_NULL
+    assert L.ulsnn_mlp_loss(C.byref(d), p, p, p, z, 8, p) == E_NULL          # labels missing
+    assert L.ulsnn_mlp_loss(C.byref(d), p, p, p, p, -1, p) == E_DIM
+    assert L.ulsnn_mlp_loss(C.byref(d), p, p, p, p, 8, p) == E_WS            # needs the workspace
+    assert L.ulsnn_mlp_grad_mse(C.byref(d), p, p, p, z, 8, p, p, p) == E_NULL   # targets missing
+    assert L.ulsnn_mlp_grad_mse(C.byref(_desc(operand_dtype=1)), p, p, p, p, 8, p, p, p) == E_UNSUP
+    assert L.ulsnn_mlp_mse(C.byref(_desc(operand_dtype=1)), p, p, p, p, 8, p) == E_UNSUP
+    assert L.ulsnn_mlp_grad_mse(C.byref(d), p, p, p, p, 8, p, p, p) == E_WS
 
 
 def test_workspace_query():
