@@ -172,6 +172,9 @@ hipError_t launch_gemm(const GemmPlan &p, bool a_kc, bool b_kc, int epi, GemmArg
         switch (epi) {
             case EPI_AXPBY: return launch_layout<Cfg, EPI_AXPBY>(a_kc, b_kc, a, splits, s);
             case EPI_PARTIAL:
+#ifdef ULSNN_TUNE
+                return launch_layout<Cfg, EPI_PARTIAL>(a_kc, b_kc, a, splits, s);
+#endif
                 if constexpr (small) {
                     if (a_kc && b_kc) return launch_one<Cfg, true, true, EPI_PARTIAL>(a, splits, s);      // NT
                     if (!a_kc && !b_kc) return launch_one<Cfg, false, false, EPI_PARTIAL>(a, splits, s);  // TN
@@ -871,6 +874,33 @@ int ulsnn_mlp_grad_describe_plan(const ulsnn_mlp_desc *desc, int batch, char *bu
     }
     return ULSNN_OK;
 }
+
+#ifdef ULSNN_TUNE
+// Tuning builds only: one product with the tile shape and k split forced (partials + reduction when split).
+int ulsnn_tune_gemm(int cfg, int splits, char transa, char transb, int m, int n, int k, const float *A, int lda,
+                    const float *B, int ldb, float *C, int ldc, float *partial, void *hip_stream)
+{
+    if (cfg < 0 || cfg >= CFG_COUNT || splits < 1 || m < 1 || n < 1 || k < 1) return ULSNN_ERR_DIM;
+    const CfgInfo &c = CFG_INFO[cfg];
+    GemmPlan p{};
+    p.cfg = (CfgId)cfg;
+    p.tiles_m = (m + c.bm - 1) / c.bm;
+    p.tiles_n = (n + c.bn - 1) / c.bn;
+    p.kchunk = (int)round_up((size_t)(k + splits - 1) / splits, c.bk);
+    p.splits = (k + p.kchunk - 1) / p.kchunk;
+    hipStream_t s = (hipStream_t)hip_stream;
+    GemmArgs a{};
+    a.A = A; a.B = B; a.C = C; a.M = m; a.N = n; a.K = k; a.lda = lda; a.ldb = ldb; a.ldc = ldc;
+    a.alpha = 1.0f; a.beta = 0.0f;
+    if (p.splits == 1)
+        return launch_gemm(p, is_n(transa), is_t(transb), EPI_AXPBY, a, s) == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
+    if (!partial) return ULSNN_ERR_NULL;
+    GemmArgs q = a;
+    q.C = partial; q.partial_stride = (size_t)m * n;
+    if (launch_gemm(p, is_n(transa), is_t(transb), EPI_PARTIAL, q, s) != hipSuccess) return ULSNN_ERR_HIP;
+    return launch_reduce(p.splits, EPI_AXPBY, a, partial, s) == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
+}
+#endif
 
 double ulsnn_sgemm_flops(int m, int n, int k) { return 2.0 * (double)m * (double)n * (double)k; }
 
