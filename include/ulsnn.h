@@ -185,6 +185,32 @@ int ulsnn_mlp_grad_timed(const ulsnn_mlp_desc *desc, const void *W1, const void 
  */
 int ulsnn_mlp_grad_describe_plan(const ulsnn_mlp_desc *desc, int batch, char *buf, size_t buf_bytes);
 
+/*
+ * The same operation as ulsnn_sgemm (section 3.1) with the blocking chosen by the caller instead of the built-in
+ * planner (for autotuning, and for tests that must reach every tile shape): `tile_shape` is one of
+ * ULSNN_TILE_*, `k_splits` >= 1 the number of slices the k range is cut into (slices are rounded up to the k
+ * step of 16, so fewer may remain).  With more than one slice the partial products go to `workspace` (device
+ * memory, 256-byte aligned, at least k_splits*m*n*4 bytes; else ULSNN_ERR_WORKSPACE) and are added in slice
+ * order, so results are deterministic.  Argument rules, layout, ownership and error behaviour otherwise as
+ * for ulsnn_sgemm.
+ */
+#define ULSNN_TILE_256x128 0   /* 8 wavefronts */
+#define ULSNN_TILE_128x128_W8 1 /* 8 wavefronts */
+#define ULSNN_TILE_128x128 2   /* 4 wavefronts */
+#define ULSNN_TILE_128x64 3
+#define ULSNN_TILE_64x128 4
+#define ULSNN_TILE_64x64 5
+#define ULSNN_TILE_COUNT 6
+int ulsnn_sgemm_planned(int tile_shape, int k_splits, char transa, char transb, int m, int n, int k, float alpha,
+                        const float *A, int lda, const float *B, int ldb, float beta, float *C, int ldc,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Host-only diagnostic: the tile shape, tile grid and modelled time ulsnn_sgemm would use for this product
+ * (section 3.1's operation), one line in the format of the lines above.  Launches nothing.
+ */
+int ulsnn_sgemm_describe_plan(char transa, char transb, int m, int n, int k, char *buf, size_t buf_bytes);
+
 /* Counting conventions (host-only): 2mnk (section 3.1) and batch*(4 n_in n_hid + 6 n_hid n_out) (section 6.2). */
 double ulsnn_sgemm_flops(int m, int n, int k);
 double ulsnn_mlp_grad_flops(int n_in, int n_hid, int n_out, int64_t batch);

@@ -10,6 +10,9 @@ from .binding import (  # noqa: F401
     load,
     mlp_grad,
     mlp_grad_describe_plan,
+    sgemm_describe_plan,
+    sgemm_planned,
+    TILE_SHAPES,
     mlp_grad_epoch,
     mlp_grad_flops,
     mlp_grad_mse,

@@ -63,6 +63,11 @@ def load():
     L.ulsnn_mlp_mse.restype = i
     L.ulsnn_mlp_loss_flops.argtypes = [i, i, i, C.c_int64]
     L.ulsnn_mlp_loss_flops.restype = C.c_double
+    L.ulsnn_sgemm_planned.argtypes = [i, i, C.c_char, C.c_char, i, i, i, C.c_float, vp, i, vp, i, C.c_float, vp, i, vp,
+                                      C.c_size_t, vp]
+    L.ulsnn_sgemm_planned.restype = i
+    L.ulsnn_sgemm_describe_plan.argtypes = [C.c_char, C.c_char, i, i, i, C.c_char_p, C.c_size_t]
+    L.ulsnn_sgemm_describe_plan.restype = i
     L.ulsnn_mlp_grad_describe_plan.argtypes = [C.POINTER(_MlpDesc), i, C.c_char_p, C.c_size_t]
     L.ulsnn_mlp_grad_describe_plan.restype = i
     L.ulsnn_sgemm_flops.argtypes = [i, i, i]
@@ -124,6 +129,26 @@ def sgemm(transa: str, transb: str, m: int, n: int, k: int, alpha: float, A: tor
         raise UlsnnError(rc, "ulsnn_sgemm")
 
 
+TILE_SHAPES = ("256x128", "128x128w8", "128x128", "128x64", "64x128", "64x64")   # index = ULSNN_TILE_*
+
+
+def sgemm_planned(tile_shape: int, k_splits: int, transa: str, transb: str, m: int, n: int, k: int, alpha: float,
+                  A: torch.Tensor, lda: int, B: torch.Tensor, ldb: int, beta: float, Cmat: torch.Tensor, ldc: int,
+                  workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """ulsnn_sgemm_planned: SGEMM with the tile shape and k split chosen by the caller."""
+    for t, nm in ((A, "A"), (B, "B"), (Cmat, "C")):
+        if t is not None:
+            _dev_f32(t, nm)
+    if workspace is None and k_splits > 1:
+        workspace = torch.empty(max(k_splits * m * n * 4, 256), dtype=torch.uint8, device=Cmat.device)
+    rc = load().ulsnn_sgemm_planned(tile_shape, k_splits, transa.encode()[:1], transb.encode()[:1], m, n, k, alpha,
+                                    _ptr(A), lda, _ptr(B), ldb, beta, _ptr(Cmat), ldc, _ptr(workspace),
+                                    0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                    _stream(stream))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_sgemm_planned")
+
+
 def _desc(n_in, n_hid, n_out, b1, b2, db1, db2, accumulate, workspace, stream, operand_dtype=0) -> _MlpDesc:
     d = _MlpDesc()
     d.n_in, d.n_hid, d.n_out = n_in, n_hid, n_out
@@ -142,6 +167,15 @@ def mlp_grad_workspace_bytes(n_in: int, n_hid: int, n_out: int, batch: int, oper
     d.n_in, d.n_hid, d.n_out = n_in, n_hid, n_out
     d.operand_dtype = operand_dtype
     return int(load().ulsnn_mlp_grad_workspace_bytes(C.byref(d), batch))
+
+
+def sgemm_describe_plan(transa: str, transb: str, m: int, n: int, k: int) -> str:
+    """Tile shape and grid ulsnn_sgemm would use (host only)."""
+    buf = C.create_string_buffer(256)
+    rc = load().ulsnn_sgemm_describe_plan(transa.encode(), transb.encode(), m, n, k, buf, len(buf))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_sgemm_describe_plan")
+    return buf.value.decode()
 
 
 def mlp_grad_describe_plan(n_in: int, n_hid: int, n_out: int, batch: int) -> str:

@@ -208,20 +208,36 @@ __device__ __forceinline__ float tanh_f32(float x)
 // Per-thread state of the unchecked fetch used for full k blocks.  The tile's base pointer (uniform) already
 // points at (first row of the tile, first k of the workgroup); `off` is this thread's element offset from it
 // and never changes, the base advances by BK (KC) or BK*ld (MC) per step.  A 16-byte load that lies wholly
-// beyond the matrix edge is redirected to a valid address (row clamped for KC, first column of the tile for
-// MC): its values only reach accumulators that are never stored.  Only an MC load that STRADDLES the edge
-// (possible when the valid width is not a multiple of 4) needs guarded 4-byte loads: bit set in `edge`.
+// beyond the matrix edge is redirected to a valid address (row clamped for KC; for MC the first column of the
+// tile, or the load that ends at the edge): its values only reach accumulators that are never stored.  An MC
+// load that STRADDLES the edge (valid width not a multiple of 4; bit set in `edge`) is replaced by the 16-byte
+// load that ENDS at the edge, and finish() moves its valid elements into place before the panel is stored.
+// When the tile has fewer than 4 valid columns that load starts before the tile, so the caller moves the
+// tile's base pointer back by `back` elements and every offset is `back` larger.  Only a matrix narrower than
+// 4 falls back to guarded 4-byte loads.  No load ever touches an address outside the rows of the matrix.
 template <bool KC, int R, int BK, int THREADS, int NV>
 struct FastFetch {
     unsigned off[NV];
     unsigned edge;
-    int valid;   // rows/columns of this tile inside the matrix
+    int valid;      // rows/columns of this tile inside the matrix
+    int back;       // elements the caller must move the base pointer back (0 or 4)
+    bool shifted;   // straddling loads are whole loads ending at the edge
 
     __device__ __forceinline__ void init(int ld, int r0, int rmax, int tid)
     {
         constexpr int TOTAL = R * BK / 4;
         edge = 0;
         valid = rmax - r0;
+        back = 0;
+        shifted = false;
+        if (!KC && valid < R && (valid & 3) != 0) {
+            if (valid >= 4) {
+                shifted = true;
+            } else if (r0 >= 4) {
+                shifted = true;
+                back = 4;
+            }
+        }
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             int f = tid + v * THREADS;
@@ -234,9 +250,18 @@ struct FastFetch {
             } else {
                 const int krow = f / (R / 4);
                 int rq = (f % (R / 4)) * 4;
-                if (rq >= valid) rq = 0;
-                else if (rq + 3 >= valid) edge |= 1u << v;
-                off[v] = (unsigned)krow * (unsigned)ld + (unsigned)rq;
+                if (rq + 3 >= valid) {               // not wholly inside the matrix
+                    if (shifted) {
+                        if (rq < valid) edge |= 1u << v;
+                        rq = valid - 4;              // >= -3, and rq + back >= 0
+                    } else if ((valid & 3) == 0) {
+                        rq = 0;                      // wholly outside, and the tile has >= 4 valid columns
+                    } else {
+                        edge |= 1u << v;             // guarded loads (they load nothing when wholly outside)
+                        if (rq >= valid) rq = 0;
+                    }
+                }
+                off[v] = (unsigned)krow * (unsigned)ld + (unsigned)(rq + back);
             }
         }
     }
@@ -246,7 +271,7 @@ struct FastFetch {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const float *src = base + off[v];
-            if (KC || !(edge >> v & 1)) {
+            if (KC || shifted || !(edge >> v & 1)) {
                 reg[v] = load4_any_align(src);
             } else {
                 const int rq = ((tid + v * THREADS) % (R / 4)) * 4;
@@ -256,6 +281,29 @@ struct FastFetch {
                 if (rq + 2 < valid) val.z = src[2];
                 reg[v] = val;
             }
+        }
+    }
+
+    // After fetch(), before the registers are stored to LDS: a straddling vector was loaded from the address
+    // 4 - valid%4 elements lower, so its valid elements sit at the top of the register; move them down.
+    // Written with selects only (no branches on valid%4).
+    __device__ __forceinline__ void finish(floatx4 (&reg)[NV]) const
+    {
+        if (KC || !shifted || edge == 0) return;
+        const bool r1 = (valid & 3) == 1, r2 = (valid & 3) == 2;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const bool e = (edge >> v & 1) != 0;
+            const floatx4 l = reg[v];
+            floatx4 o;
+            o.x = r1 ? l.w : (r2 ? l.z : l.y);
+            o.y = r1 ? 0.f : (r2 ? l.w : l.z);
+            o.z = (r1 || r2) ? 0.f : l.w;
+            o.w = 0.f;
+            reg[v].x = e ? o.x : l.x;
+            reg[v].y = e ? o.y : l.y;
+            reg[v].z = e ? o.z : l.z;
+            reg[v].w = e ? o.w : l.w;
         }
     }
 };
@@ -352,6 +400,8 @@ __device__ __forceinline__ void gemm_segment(const GemmArgs &g, const int tile_m
     // uniform base pointers of the tile at k = kbeg, and their advance per step
     const float *pa = A_KC ? g.A + (size_t)i0 * g.lda + kbeg : g.A + (size_t)kbeg * g.lda + i0;
     const float *pb = B_KC ? g.B + (size_t)j0 * g.ldb + kbeg : g.B + (size_t)kbeg * g.ldb + j0;
+    pa -= fa.back;
+    pb -= fb.back;
     const size_t step_a = A_KC ? (size_t)BK : (size_t)BK * g.lda;
     const size_t step_b = B_KC ? (size_t)BK : (size_t)BK * g.ldb;
 
@@ -367,6 +417,8 @@ __device__ __forceinline__ void gemm_segment(const GemmArgs &g, const int tile_m
         if (nfull > 0) {
             fa.fetch(ra, pa, tid);
             fb.fetch(rb, pb, tid);
+            fa.finish(ra);
+            fb.finish(rb);
         } else {
             panel_fetch<A_KC, BM, BK, THREADS, NVA>(ra, g.A, g.lda, i0, g.M, kbeg, kend, tid);
             panel_fetch<B_KC, BN, BK, THREADS, NVB>(rb, g.B, g.ldb, j0, g.N, kbeg, kend, tid);
@@ -397,6 +449,8 @@ __device__ __forceinline__ void gemm_segment(const GemmArgs &g, const int tile_m
         fa.fetch(ra, pa, tid);
         fb.fetch(rb, pb, tid);
         compute(cur);
+        fa.finish(ra);
+        fb.finish(rb);
         panel_store<A_KC, BM, BK, THREADS, NVA>(stage_a(cur ^ 1), ra, tid);
         panel_store<B_KC, BN, BK, THREADS, NVB>(stage_b(cur ^ 1), rb, tid);
         __syncthreads();

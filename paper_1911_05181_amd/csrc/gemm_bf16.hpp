@@ -146,8 +146,12 @@ struct FastFetch16 {
             } else {
                 const int krow = f / (R / 8);
                 int rq = (f % (R / 8)) * 8;
-                if (rq >= valid) rq = 0;
-                else if (rq + 7 >= valid) edge |= 1u << v;
+                if (rq >= valid) {
+                    rq = 0;
+                    if (valid < 8) edge |= 1u << v;   // first vector of the tile straddles too: load nothing
+                } else if (rq + 7 >= valid) {
+                    edge |= 1u << v;
+                }
                 off[v] = (unsigned)krow * (unsigned)ld + (unsigned)rq;
             }
         }

@@ -168,18 +168,9 @@ hipError_t launch_gemm(const GemmPlan &p, bool a_kc, bool b_kc, int epi, GemmArg
     const int splits = p.splits;
     return with_cfg(p.cfg, [&](auto cfg) -> hipError_t {
         using Cfg = decltype(cfg);
-        constexpr bool small = Cfg::THREADS == 256;
         switch (epi) {
             case EPI_AXPBY: return launch_layout<Cfg, EPI_AXPBY>(a_kc, b_kc, a, splits, s);
-            case EPI_PARTIAL:
-#ifdef ULSNN_TUNE
-                return launch_layout<Cfg, EPI_PARTIAL>(a_kc, b_kc, a, splits, s);
-#endif
-                if constexpr (small) {
-                    if (a_kc && b_kc) return launch_one<Cfg, true, true, EPI_PARTIAL>(a, splits, s);      // NT
-                    if (!a_kc && !b_kc) return launch_one<Cfg, false, false, EPI_PARTIAL>(a, splits, s);  // TN
-                }
-                return hipErrorInvalidValue;
+            case EPI_PARTIAL: return launch_layout<Cfg, EPI_PARTIAL>(a_kc, b_kc, a, splits, s);
             case EPI_BIAS_TANH: return launch_one<Cfg, true, false, EPI_BIAS_TANH>(a, splits, s);   // NN only
             case EPI_BIAS: return launch_one<Cfg, true, false, EPI_BIAS>(a, splits, s);             // NN only
             default: return launch_one<Cfg, true, true, EPI_TANHGRAD>(a, splits, s);                // NT only
@@ -875,32 +866,52 @@ int ulsnn_mlp_grad_describe_plan(const ulsnn_mlp_desc *desc, int batch, char *bu
     return ULSNN_OK;
 }
 
-#ifdef ULSNN_TUNE
-// Tuning builds only: one product with the tile shape and k split forced (partials + reduction when split).
-int ulsnn_tune_gemm(int cfg, int splits, char transa, char transb, int m, int n, int k, const float *A, int lda,
-                    const float *B, int ldb, float *C, int ldc, float *partial, void *hip_stream)
+int ulsnn_sgemm_describe_plan(char transa, char transb, int m, int n, int k, char *buf, size_t buf_bytes)
 {
-    if (cfg < 0 || cfg >= CFG_COUNT || splits < 1 || m < 1 || n < 1 || k < 1) return ULSNN_ERR_DIM;
-    const CfgInfo &c = CFG_INFO[cfg];
+    if (!buf) return ULSNN_ERR_NULL;
+    if (!(is_n(transa) || is_t(transa)) || !(is_n(transb) || is_t(transb))) return ULSNN_ERR_TRANS;
+    if (m < 1 || n < 1 || k < 1 || buf_bytes < 1) return ULSNN_ERR_DIM;
+    const GemmPlan p = plan_gemm(m, n, k, is_n(transa), is_t(transb), false, ALL_CFGS);
+    snprintf(buf, buf_bytes, "tile=%s tiles=%dx%d splits=%d kchunk=%d model_us=%.1f\n", CFG_INFO[p.cfg].name,
+             p.tiles_m, p.tiles_n, p.splits, p.kchunk, p.est_us);
+    return ULSNN_OK;
+}
+
+int ulsnn_sgemm_planned(int tile_shape, int k_splits, char transa, char transb, int m, int n, int k, float alpha,
+                        const float *A, int lda, const float *B, int ldb, float beta, float *C, int ldc,
+                        void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!(is_n(transa) || is_t(transa)) || !(is_n(transb) || is_t(transb))) return ULSNN_ERR_TRANS;
+    if (tile_shape < 0 || tile_shape >= CFG_COUNT || k_splits < 1 || m < 0 || n < 0 || k < 0) return ULSNN_ERR_DIM;
+    const int cols_a = is_n(transa) ? k : m;
+    const int cols_b = is_n(transb) ? n : k;
+    if (lda < std::max(1, cols_a) || ldb < std::max(1, cols_b) || ldc < std::max(1, n)) return ULSNN_ERR_LD;
+    if (m == 0 || n == 0) return ULSNN_OK;
+    if (!C) return ULSNN_ERR_NULL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (k == 0 || alpha == 0.0f)
+        return ulsnn_sgemm(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, hip_stream);
+    if (!A || !B) return ULSNN_ERR_NULL;
+    const CfgInfo &c = CFG_INFO[tile_shape];
     GemmPlan p{};
-    p.cfg = (CfgId)cfg;
+    p.cfg = (CfgId)tile_shape;
     p.tiles_m = (m + c.bm - 1) / c.bm;
     p.tiles_n = (n + c.bn - 1) / c.bn;
-    p.kchunk = (int)round_up((size_t)(k + splits - 1) / splits, c.bk);
+    p.kchunk = (int)round_up((size_t)(k + k_splits - 1) / k_splits, c.bk);
     p.splits = (k + p.kchunk - 1) / p.kchunk;
-    hipStream_t s = (hipStream_t)hip_stream;
     GemmArgs a{};
     a.A = A; a.B = B; a.C = C; a.M = m; a.N = n; a.K = k; a.lda = lda; a.ldb = ldb; a.ldc = ldc;
-    a.alpha = 1.0f; a.beta = 0.0f;
+    a.alpha = alpha; a.beta = beta;
     if (p.splits == 1)
         return launch_gemm(p, is_n(transa), is_t(transb), EPI_AXPBY, a, s) == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
-    if (!partial) return ULSNN_ERR_NULL;
+    const size_t need = (size_t)p.splits * m * n * sizeof(float);
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need) return ULSNN_ERR_WORKSPACE;
     GemmArgs q = a;
-    q.C = partial; q.partial_stride = (size_t)m * n;
+    q.C = (float *)workspace;
+    q.partial_stride = (size_t)m * n;
     if (launch_gemm(p, is_n(transa), is_t(transb), EPI_PARTIAL, q, s) != hipSuccess) return ULSNN_ERR_HIP;
-    return launch_reduce(p.splits, EPI_AXPBY, a, partial, s) == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
+    return launch_reduce(p.splits, EPI_AXPBY, a, (const float *)workspace, s) == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
 }
-#endif
 
 double ulsnn_sgemm_flops(int m, int n, int k) { return 2.0 * (double)m * (double)n * (double)k; }
 

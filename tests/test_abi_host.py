@@ -106,6 +106,28 @@ def test_mlp_grad_argument_errors():
     assert L.ulsnn_mlp_grad_epoch(C.byref(_desc()), p, p, p, p, 100, 10, p, p, p) == E_WS
 
 
+def test_sgemm_planned_argument_errors_and_plan_description():
+    L = ulsnn.load()
+    p = C.c_void_p(0x1000)
+    f = lambda tile, sp, ta, tb, m, n, k, ws=None, wsb=0: L.ulsnn_sgemm_planned(
+        tile, sp, ta, tb, m, n, k, 1.0, p, max(k, m, 1), p, max(n, k, 1), 0.0, p, max(n, 1), ws, wsb, None)
+    assert f(6, 1, b"N", b"N", 8, 8, 8) == E_DIM           # no such tile shape
+    assert f(-1, 1, b"N", b"N", 8, 8, 8) == E_DIM
+    assert f(0, 0, b"N", b"N", 8, 8, 8) == E_DIM           # k_splits < 1
+    assert f(0, 1, b"X", b"N", 8, 8, 8) == E_TRANS
+    assert f(0, 1, b"N", b"N", 0, 8, 8) == OK              # empty product: nothing to do
+    assert f(2, 4, b"N", b"N", 64, 64, 256) == E_WS        # split without workspace
+    assert f(2, 4, b"N", b"N", 64, 64, 256, C.c_void_p(0x1000), 100) == E_WS   # too small
+    assert f(2, 4, b"N", b"N", 64, 64, 256, C.c_void_p(0x1010), 1 << 20) == E_WS   # misaligned
+    assert L.ulsnn_sgemm_planned(0, 1, b"N", b"N", 8, 8, 8, 1.0, p, 4, p, 8, 0.0, p, 8, None, 0, None) == E_LD
+    line = ulsnn.sgemm_describe_plan("N", "T", 8192, 8192, 8192)
+    assert line.startswith("tile=256x128 ") and "splits=1" in line
+    assert ulsnn.sgemm_describe_plan("N", "N", 64, 64, 64).startswith("tile=64x64 ")
+    buf = C.create_string_buffer(8)
+    assert L.ulsnn_sgemm_describe_plan(b"N", b"N", 0, 8, 8, buf, 8) == E_DIM
+    assert L.ulsnn_sgemm_describe_plan(b"N", b"N", 8, 8, 8, None, 8) == E_NULL
+
+
 def test_loss_only_and_mse_argument_errors():
     L = ulsnn.load()
     p, z = C.c_void_p(0x1000), C.c_void_p(0)

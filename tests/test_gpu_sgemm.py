@@ -38,7 +38,9 @@ def _run(ta, tb, m, n, k, alpha, A, lda, B, ldb, beta, C0, ldc):
 
 
 INT_SHAPES = [(1, 1, 1), (3, 5, 7), (33, 31, 9), (130, 70, 33), (257, 129, 100), (64, 48, 130), (128, 128, 16),
-              (200, 300, 17)]
+              (200, 300, 17),
+              # edges narrower than one 16-byte load, in a later tile (67 = 64 + 3) and in the only tile (3, 2)
+              (100, 67, 48), (67, 100, 48), (40, 3, 40), (2, 50, 64), (131, 134, 96)]
 
 
 @pytest.mark.parametrize("ta,tb", list(itertools.product("NT", "NT")))
@@ -149,3 +151,27 @@ def test_runs_on_a_side_stream():
     s.synchronize()
     torch.cuda.synchronize()
     assert torch.equal(got, want)
+
+
+# every tile shape x every layout on shapes whose edges are not multiples of 4 (and of the tile), with and
+# without k splits: integer matrices, so any blocking must reproduce the oracle bit for bit
+EDGE_SHAPES = [(131, 135, 96), (259, 67, 64), (70, 259, 48), (300, 3, 80), (2, 133, 64), (257, 130, 40)]
+
+
+@pytest.mark.parametrize("tile", range(len(ulsnn.TILE_SHAPES)), ids=ulsnn.TILE_SHAPES)
+@pytest.mark.parametrize("ta,tb", list(itertools.product("NT", "NT")))
+def test_every_tile_shape_on_ragged_edges(tile, ta, tb):
+    for (m, n, k) in EDGE_SHAPES:
+        (ra, ca), (rb, cb) = _stored_dims(ta, tb, m, n, k)
+        pad = 1
+        A = _padded(si.small_integers(41, si.T_A, ra, ca).numpy(), ca + pad)
+        B = _padded(si.small_integers(41, si.T_B, rb, cb).numpy(), cb + pad)
+        C0 = _padded(si.small_integers(41, si.T_C, m, n, even=True).numpy(), n + pad)
+        want = oracle.sgemm(ta, tb, m, n, k, 1.0, A, ca + pad, B, cb + pad, 0.5, C0, n + pad)
+        for splits in (1, 3):
+            dA, dB, dC = (torch.from_numpy(x).to(DEV) for x in (A, B, C0))
+            ulsnn.sgemm_planned(tile, splits, ta, tb, m, n, k, 1.0, dA, ca + pad, dB, cb + pad, 0.5, dC, n + pad)
+            torch.cuda.synchronize()
+            got = dC.cpu().numpy()
+            assert np.array_equal(got[:, :n], want[:, :n]), (ulsnn.TILE_SHAPES[tile], ta, tb, m, n, k, splits)
+            assert np.isnan(got[:, n:]).all()
