@@ -186,6 +186,57 @@ int ulsnn_mlp_grad_timed(const ulsnn_mlp_desc *desc, const void *W1, const void 
 int ulsnn_mlp_grad_describe_plan(const ulsnn_mlp_desc *desc, int batch, char *buf, size_t buf_bytes);
 
 /*
+ * Optimiser step (section 4.2, last paragraph).  The paper names the ingredients -- the plain step
+ * W := W - alpha grad E, the Polak-Ribiere conjugate-gradient direction, a line search built from an exponential
+ * step-size scheme, a quadratic interpolation and a bracketing test on the SIGN of grad E . direction estimated
+ * from few patterns -- without printing an algorithm; the functions below fix one.  All vectors are dense fp32
+ * device arrays of n elements; scalar results are device floats unless stated; sums are taken in double in a
+ * fixed order (deterministic).  `workspace` of the three vector calls: device memory, 256-byte aligned, at
+ * least ULSNN_VEC_WORKSPACE_BYTES (else ULSNN_ERR_WORKSPACE).  Asynchronous on hip_stream.
+ */
+#define ULSNN_VEC_WORKSPACE_BYTES 16640
+
+/* *result = sum_i x[i]*y[i]. */
+int ulsnn_dot(int64_t n, const float *x, const float *y, float *result, void *workspace, size_t workspace_bytes,
+              void *hip_stream);
+
+/* y += alpha*x (alpha = -step, x = grad E gives the plain gradient step). */
+int ulsnn_axpy(int64_t n, float alpha, const float *x, float *y, void *hip_stream);
+
+/*
+ * Polak-Ribiere direction: beta = g_new.(g_new - g_old) / g_old.g_old (0 if the denominator is 0), then
+ * d := -g_new + beta*d in place.  g_old == NULL starts (or restarts) the sequence: d := -g_new, beta = 0 and d is
+ * not read.  `beta`, if not NULL, receives the coefficient (device float).
+ */
+int ulsnn_cg_direction(int64_t n, const float *g_new, const float *g_old, float *d, float *beta, void *workspace,
+                       size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Line search along (d1, d2) for the softmax / cross-entropy network without biases, fp32 (biases or bf16
+ * operands: ULSNN_ERR_UNSUPPORTED).  E0 = E(W) on all `batch` patterns.  Steps alpha_k = alpha0 * 2^k,
+ * k = 0..max_doublings (<= 60): the first k at which grad E_sub(W + alpha_k d) . d >= 0, the gradient taken on the
+ * first min(bracket_batch, batch) patterns only, closes the bracket [lo, hi] = [alpha_(k-1) or 0, alpha_k]; if none
+ * does, the last two steps are the bracket.  E is evaluated (all patterns) at lo (E0 if lo = 0), (lo + hi)/2 and
+ * hi; if the parabola through these is convex, also at its vertex clamped to the bracket.  The step with the
+ * smallest E among those evaluated is applied: W := W + alpha d in place (W unchanged if that step is 0).
+ * `result` is HOST memory; the call synchronises hip_stream after every evaluation (it must read the scalars to
+ * decide).  desc->workspace must hold ulsnn_mlp_line_search_workspace_bytes(desc, batch) bytes (the gradient
+ * workspace for `batch` patterns plus two weight-sized and two gradient-sized arrays); desc->accumulate is ignored.
+ */
+typedef struct {
+    float alpha;               /* step applied */
+    float loss;                /* E at that step */
+    float loss0;               /* E before the step */
+    float bracket_lo, bracket_hi;
+    int error_evaluations;     /* forward-only passes over all patterns */
+    int gradient_evaluations;  /* gradients on the bracketing subset */
+} ulsnn_line_search_result;
+size_t ulsnn_mlp_line_search_workspace_bytes(const ulsnn_mlp_desc *desc, int batch);
+int ulsnn_mlp_line_search(const ulsnn_mlp_desc *desc, float *W1, float *W2, const float *d1, const float *d2,
+                          const float *X, const int32_t *labels, int batch, int bracket_batch, float alpha0,
+                          int max_doublings, ulsnn_line_search_result *result);
+
+/*
  * The same operation as ulsnn_sgemm (section 3.1) with the blocking chosen by the caller instead of the built-in
  * planner (for autotuning, and for tests that must reach every tile shape): `tile_shape` is one of
  * ULSNN_TILE_*, `k_splits` >= 1 the number of slices the k range is cut into (slices are rounded up to the k

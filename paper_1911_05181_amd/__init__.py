@@ -11,6 +11,13 @@ from .binding import (  # noqa: F401
     mlp_grad,
     mlp_grad_describe_plan,
     sgemm_describe_plan,
+    dot,
+    axpy,
+    cg_direction,
+    mlp_line_search,
+    mlp_line_search_workspace_bytes,
+    LineSearchResult,
+    VEC_WORKSPACE_BYTES,
     sgemm_planned,
     TILE_SHAPES,
     mlp_grad_epoch,

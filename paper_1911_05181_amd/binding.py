@@ -30,6 +30,15 @@ class _MlpDesc(C.Structure):
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("hip_stream", C.c_void_p)]
 
 
+class LineSearchResult(C.Structure):
+    """ulsnn_line_search_result (host memory)."""
+    _fields_ = [("alpha", C.c_float), ("loss", C.c_float), ("loss0", C.c_float), ("bracket_lo", C.c_float),
+                ("bracket_hi", C.c_float), ("error_evaluations", C.c_int), ("gradient_evaluations", C.c_int)]
+
+
+VEC_WORKSPACE_BYTES = 16640   # ULSNN_VEC_WORKSPACE_BYTES
+
+
 def lib_path() -> str:
     return os.path.join(_HERE, _LIB_NAME)
 
@@ -63,6 +72,17 @@ def load():
     L.ulsnn_mlp_mse.restype = i
     L.ulsnn_mlp_loss_flops.argtypes = [i, i, i, C.c_int64]
     L.ulsnn_mlp_loss_flops.restype = C.c_double
+    L.ulsnn_dot.argtypes = [C.c_int64, vp, vp, vp, vp, C.c_size_t, vp]
+    L.ulsnn_dot.restype = i
+    L.ulsnn_axpy.argtypes = [C.c_int64, f, vp, vp, vp]
+    L.ulsnn_axpy.restype = i
+    L.ulsnn_cg_direction.argtypes = [C.c_int64, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    L.ulsnn_cg_direction.restype = i
+    L.ulsnn_mlp_line_search_workspace_bytes.argtypes = [C.POINTER(_MlpDesc), i]
+    L.ulsnn_mlp_line_search_workspace_bytes.restype = C.c_size_t
+    L.ulsnn_mlp_line_search.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, vp, vp, i, i, f, i,
+                                        C.POINTER(LineSearchResult)]
+    L.ulsnn_mlp_line_search.restype = i
     L.ulsnn_sgemm_planned.argtypes = [i, i, C.c_char, C.c_char, i, i, i, C.c_float, vp, i, vp, i, C.c_float, vp, i, vp,
                                       C.c_size_t, vp]
     L.ulsnn_sgemm_planned.restype = i
@@ -127,6 +147,82 @@ def sgemm(transa: str, transb: str, m: int, n: int, k: int, alpha: float, A: tor
                             beta, _ptr(Cmat), ldc, _stream(stream))
     if rc:
         raise UlsnnError(rc, "ulsnn_sgemm")
+
+
+def _vec_ws(workspace, device):
+    if workspace is None:
+        workspace = torch.empty(VEC_WORKSPACE_BYTES, dtype=torch.uint8, device=device)
+    return workspace
+
+
+def dot(x: torch.Tensor, y: torch.Tensor, *, out: Optional[torch.Tensor] = None, workspace=None, stream=None):
+    """sum x*y over all elements (ulsnn_dot); returns a one-element device tensor."""
+    _dev_f32(x, "x"), _dev_f32(y, "y")
+    if x.numel() != y.numel() or not (x.is_contiguous() and y.is_contiguous()):
+        raise ValueError("dot: contiguous tensors of equal size")
+    if out is None:
+        out = torch.empty(1, device=x.device)
+    workspace = _vec_ws(workspace, x.device)
+    rc = load().ulsnn_dot(x.numel(), _ptr(x), _ptr(y), _ptr(out), _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_dot")
+    return out
+
+
+def axpy(alpha: float, x: torch.Tensor, y: torch.Tensor, stream=None) -> torch.Tensor:
+    """y += alpha*x in place (ulsnn_axpy)."""
+    _dev_f32(x, "x"), _dev_f32(y, "y")
+    if x.numel() != y.numel() or not (x.is_contiguous() and y.is_contiguous()):
+        raise ValueError("axpy: contiguous tensors of equal size")
+    rc = load().ulsnn_axpy(x.numel(), alpha, _ptr(x), _ptr(y), _stream(stream))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_axpy")
+    return y
+
+
+def cg_direction(g_new: torch.Tensor, g_old: Optional[torch.Tensor], d: torch.Tensor, *, beta=None, workspace=None,
+                 stream=None):
+    """Polak-Ribiere update of the direction d in place (ulsnn_cg_direction); returns (d, beta device tensor)."""
+    _dev_f32(g_new, "g_new"), _dev_f32(d, "d")
+    if g_old is not None:
+        _dev_f32(g_old, "g_old")
+    for t in (g_new, d) + ((g_old,) if g_old is not None else ()):
+        if t.numel() != g_new.numel() or not t.is_contiguous():
+            raise ValueError("cg_direction: contiguous tensors of equal size")
+    if beta is None:
+        beta = torch.empty(1, device=d.device)
+    workspace = _vec_ws(workspace, d.device)
+    rc = load().ulsnn_cg_direction(g_new.numel(), _ptr(g_new), _ptr(g_old), _ptr(d), _ptr(beta), _ptr(workspace),
+                                   workspace.numel(), _stream(stream))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_cg_direction")
+    return d, beta
+
+
+def mlp_line_search_workspace_bytes(n_in: int, n_hid: int, n_out: int, batch: int) -> int:
+    d = _desc(n_in, n_hid, n_out, None, None, None, None, False, None, None)
+    return int(load().ulsnn_mlp_line_search_workspace_bytes(C.byref(d), batch))
+
+
+def mlp_line_search(W1, W2, d1, d2, X, labels, bracket_batch: int, alpha0: float, max_doublings: int, *,
+                    workspace: Optional[torch.Tensor] = None, stream=None) -> LineSearchResult:
+    """Line search along (d1, d2); updates W1, W2 in place (ulsnn_mlp_line_search).  Synchronises the stream."""
+    n_in, n_hid, n_out, _, odt = _mlp_common(W1, W2, X, labels, None, None, MlpGradResult(None, None, None), False)
+    for t, ref, nm in ((d1, W1, "d1"), (d2, W2, "d2")):
+        _dev_f32(t, nm)
+        if t.shape != ref.shape or not t.is_contiguous():
+            raise ValueError(f"{nm} must be contiguous and shaped like its weight matrix")
+    batch = X.shape[0]
+    if workspace is None:
+        workspace = torch.empty(max(mlp_line_search_workspace_bytes(n_in, n_hid, n_out, batch), 256), dtype=torch.uint8,
+                                device=W1.device)
+    d = _desc(n_in, n_hid, n_out, None, None, None, None, False, workspace, stream, odt)
+    res = LineSearchResult()
+    rc = load().ulsnn_mlp_line_search(C.byref(d), _ptr(W1), _ptr(W2), _ptr(d1), _ptr(d2), _ptr(X), _ptr(labels), batch,
+                                      bracket_batch, alpha0, max_doublings, C.byref(res))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_mlp_line_search")
+    return res
 
 
 TILE_SHAPES = ("256x128", "128x128w8", "128x128", "128x64", "64x128", "64x64")   # index = ULSNN_TILE_*

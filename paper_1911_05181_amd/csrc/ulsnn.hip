@@ -12,6 +12,7 @@
 #include "gemm.hpp"
 #include "gemm_bf16.hpp"
 #include "mlp_kernels.hpp"
+#include "vec_kernels.hpp"
 
 using namespace ulsnn;
 
@@ -843,6 +844,221 @@ int ulsnn_mlp_grad_timed(const ulsnn_mlp_desc *desc, const void *W1, const void 
             if (hipEventElapsedTime(&stage_ms[i], ev[i], ev[i + 1]) != hipSuccess) out = ULSNN_ERR_HIP;
     for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
     return out;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Optimiser step (section 4.2, last paragraph): vector primitives, Polak-Ribiere direction, line search
+// ---------------------------------------------------------------------------------------------------------
+
+namespace {
+
+inline unsigned vec_grid(size_t n) { return (unsigned)std::min<size_t>((n + 255) / 256, (size_t)VEC_MAX_BLOCKS); }
+
+inline bool vec_ws_ok(const void *ws, size_t bytes)
+{
+    return ws && ((uintptr_t)ws & 255) == 0 && bytes >= (size_t)ULSNN_VEC_WORKSPACE_BYTES;
+}
+
+// *out (device) = x . y
+hipError_t launch_dot(size_t n, const float *x, const float *y, float *out, double *partial, hipStream_t s)
+{
+    const unsigned nb = vec_grid(n);
+    hipLaunchKernelGGL(dot_partial_kernel<false>, dim3(nb), dim3(256), 0, s, n, x, y, partial);
+    hipLaunchKernelGGL(dot_final_kernel<false>, dim3(1), dim3(256), 0, s, (const double *)partial, (int)nb, out);
+    return hipGetLastError();
+}
+
+struct LsLayout {
+    size_t mlp_bytes, n1, n2;
+    size_t off_w1, off_w2, off_g1, off_g2, off_vec, off_scalars, bytes;
+};
+
+LsLayout ls_layout(const ulsnn_mlp_desc *d, int batch)
+{
+    LsLayout L{};
+    L.mlp_bytes = round_up(mlp_layout(d, batch).bytes, 256);
+    L.n1 = (size_t)d->n_in * d->n_hid;
+    L.n2 = (size_t)d->n_hid * d->n_out;
+    size_t off = L.mlp_bytes;
+    L.off_w1 = off; off += round_up(L.n1 * 4, 256);
+    L.off_w2 = off; off += round_up(L.n2 * 4, 256);
+    L.off_g1 = off; off += round_up(L.n1 * 4, 256);
+    L.off_g2 = off; off += round_up(L.n2 * 4, 256);
+    L.off_vec = off; off += round_up((size_t)ULSNN_VEC_WORKSPACE_BYTES, 256);
+    L.off_scalars = off; off += 256;
+    L.bytes = off;
+    return L;
+}
+
+}  // namespace
+
+int ulsnn_dot(int64_t n, const float *x, const float *y, float *result, void *workspace, size_t workspace_bytes,
+              void *hip_stream)
+{
+    if (n < 0) return ULSNN_ERR_DIM;
+    if (!result || (n > 0 && (!x || !y))) return ULSNN_ERR_NULL;
+    if (!vec_ws_ok(workspace, workspace_bytes)) return ULSNN_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (n == 0) {
+        hipLaunchKernelGGL(zero_kernel, dim3(1), dim3(256), 0, s, result, (size_t)1);
+        return hipGetLastError() == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
+    }
+    return launch_dot((size_t)n, x, y, result, (double *)workspace, s) == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
+}
+
+int ulsnn_axpy(int64_t n, float alpha, const float *x, float *y, void *hip_stream)
+{
+    if (n < 0) return ULSNN_ERR_DIM;
+    if (n == 0) return ULSNN_OK;
+    if (!x || !y) return ULSNN_ERR_NULL;
+    hipLaunchKernelGGL(add_scaled_kernel, dim3(grid_for((size_t)n)), dim3(256), 0, (hipStream_t)hip_stream, (size_t)n,
+                       (const float *)y, alpha, x, y);
+    return hipGetLastError() == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
+}
+
+int ulsnn_cg_direction(int64_t n, const float *g_new, const float *g_old, float *d, float *beta, void *workspace,
+                       size_t workspace_bytes, void *hip_stream)
+{
+    if (n < 0) return ULSNN_ERR_DIM;
+    if (n > 0 && (!g_new || !d)) return ULSNN_ERR_NULL;
+    if (!vec_ws_ok(workspace, workspace_bytes)) return ULSNN_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    double *partial = (double *)workspace;
+    float *bdev = beta ? beta : (float *)((char *)workspace + 2 * VEC_MAX_BLOCKS * sizeof(double));
+    if (n == 0 || !g_old) {
+        if (beta) hipLaunchKernelGGL(zero_kernel, dim3(1), dim3(256), 0, s, beta, (size_t)1);
+        if (n > 0)
+            hipLaunchKernelGGL(cg_update_kernel, dim3(grid_for((size_t)n)), dim3(256), 0, s, (size_t)n, g_new, d,
+                               (const float *)nullptr);
+        return hipGetLastError() == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
+    }
+    const unsigned nb = vec_grid((size_t)n);
+    hipLaunchKernelGGL(dot_partial_kernel<true>, dim3(nb), dim3(256), 0, s, (size_t)n, g_new, g_old, partial);
+    hipLaunchKernelGGL(dot_final_kernel<true>, dim3(1), dim3(256), 0, s, (const double *)partial, (int)nb, bdev);
+    hipLaunchKernelGGL(cg_update_kernel, dim3(grid_for((size_t)n)), dim3(256), 0, s, (size_t)n, g_new, d,
+                       (const float *)bdev);
+    return hipGetLastError() == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
+}
+
+size_t ulsnn_mlp_line_search_workspace_bytes(const ulsnn_mlp_desc *desc, int batch)
+{
+    if (!desc_ok(desc) || batch < 1) return 0;
+    return ls_layout(desc, batch).bytes;
+}
+
+int ulsnn_mlp_line_search(const ulsnn_mlp_desc *desc, float *W1, float *W2, const float *d1, const float *d2,
+                          const float *X, const int32_t *labels, int batch, int bracket_batch, float alpha0,
+                          int max_doublings, ulsnn_line_search_result *result)
+{
+    if (!desc || !result) return ULSNN_ERR_NULL;
+    if (!desc_ok(desc) || batch < 1 || bracket_batch < 1 || max_doublings < 0 || max_doublings > 60 ||
+        !(alpha0 > 0.0f) || !std::isfinite(alpha0))
+        return ULSNN_ERR_DIM;
+    if (!W1 || !W2 || !d1 || !d2 || !X || !labels) return ULSNN_ERR_NULL;
+    if (desc->b1 || desc->b2 || desc->db1 || desc->db2 || desc->operand_dtype != 0) return ULSNN_ERR_UNSUPPORTED;
+    const LsLayout L = ls_layout(desc, batch);
+    if (!desc->workspace || ((uintptr_t)desc->workspace & 255) != 0 || desc->workspace_bytes < L.bytes)
+        return ULSNN_ERR_WORKSPACE;
+    char *base = (char *)desc->workspace;
+    float *T1 = (float *)(base + L.off_w1), *T2 = (float *)(base + L.off_w2);
+    float *G1 = (float *)(base + L.off_g1), *G2 = (float *)(base + L.off_g2);
+    double *partial = (double *)(base + L.off_vec);
+    float *scal = (float *)(base + L.off_scalars);   // [0] loss, [1] g1.d1, [2] g2.d2
+    hipStream_t s = (hipStream_t)desc->hip_stream;
+    ulsnn_mlp_desc sub = *desc;
+    sub.workspace = base;
+    sub.workspace_bytes = L.mlp_bytes;
+    sub.accumulate = 0;
+    const int nsub = std::min(bracket_batch, batch);
+    int n_err = 0, n_grad = 0;
+
+    // weights at step alpha: the caller's own for alpha == 0, else T = W + alpha d
+    auto weights_at = [&](double alpha, const float *&w1, const float *&w2) -> hipError_t {
+        if (alpha == 0.0) {
+            w1 = W1; w2 = W2;
+            return hipSuccess;
+        }
+        hipLaunchKernelGGL(add_scaled_kernel, dim3(grid_for(L.n1)), dim3(256), 0, s, L.n1, (const float *)W1,
+                           (float)alpha, d1, T1);
+        hipLaunchKernelGGL(add_scaled_kernel, dim3(grid_for(L.n2)), dim3(256), 0, s, L.n2, (const float *)W2,
+                           (float)alpha, d2, T2);
+        w1 = T1; w2 = T2;
+        return hipGetLastError();
+    };
+    // E(W + alpha d) over all `batch` patterns (one error evaluation, section 6.2)
+    auto error_at = [&](double alpha, double &e) -> int {
+        const float *w1, *w2;
+        HIP_TRY(weights_at(alpha, w1, w2));
+        const int rc = mlp_grad_impl(&sub, w1, w2, X, MlpTask{labels, nullptr, false}, batch, nullptr, nullptr, scal,
+                                     false);
+        if (rc != ULSNN_OK) return rc;
+        float h = 0.f;
+        HIP_TRY(hipMemcpyAsync(&h, scal, sizeof(float), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        e = (double)h;
+        ++n_err;
+        return ULSNN_OK;
+    };
+    // grad E_sub(W + alpha d) . d on the first nsub patterns: only its sign is used
+    auto slope_at = [&](double alpha, double &sl) -> int {
+        const float *w1, *w2;
+        HIP_TRY(weights_at(alpha, w1, w2));
+        const int rc = mlp_grad_impl(&sub, w1, w2, X, MlpTask{labels, nullptr, true}, nsub, G1, G2, scal, false);
+        if (rc != ULSNN_OK) return rc;
+        HIP_TRY(launch_dot(L.n1, G1, d1, scal + 1, partial, s));
+        HIP_TRY(launch_dot(L.n2, G2, d2, scal + 2, partial, s));
+        float h[2] = {0.f, 0.f};
+        HIP_TRY(hipMemcpyAsync(h, scal + 1, 2 * sizeof(float), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        sl = (double)h[0] + (double)h[1];
+        ++n_grad;
+        return ULSNN_OK;
+    };
+
+    int rc;
+    double e0 = 0.0;
+    if ((rc = error_at(0.0, e0)) != ULSNN_OK) return rc;
+    double lo = 0.0, hi = alpha0, prev = 0.0;
+    for (int k = 0; k <= max_doublings; ++k) {
+        hi = (double)alpha0 * std::ldexp(1.0, k);
+        lo = prev;
+        double sl = 0.0;
+        if ((rc = slope_at(hi, sl)) != ULSNN_OK) return rc;
+        if (sl >= 0.0) break;
+        prev = hi;
+    }
+    const double mid = 0.5 * (lo + hi);
+    double e_lo = e0, e_mid = 0.0, e_hi = 0.0;
+    if (lo != 0.0 && (rc = error_at(lo, e_lo)) != ULSNN_OK) return rc;
+    if ((rc = error_at(mid, e_mid)) != ULSNN_OK) return rc;
+    if ((rc = error_at(hi, e_hi)) != ULSNN_OK) return rc;
+    double best_a = lo, best_e = e_lo;
+    if (e_mid < best_e) { best_a = mid; best_e = e_mid; }
+    if (e_hi < best_e) { best_a = hi; best_e = e_hi; }
+    const double curv = e_lo - 2.0 * e_mid + e_hi;
+    if (curv > 0.0) {
+        const double h = 0.5 * (hi - lo);
+        double q = mid - h * (e_hi - e_lo) / (2.0 * curv);
+        q = std::min(std::max(q, lo), hi);
+        double e_q = 0.0;
+        if ((rc = error_at(q, e_q)) != ULSNN_OK) return rc;
+        if (e_q < best_e) { best_a = q; best_e = e_q; }
+    }
+    if (best_a != 0.0) {
+        hipLaunchKernelGGL(add_scaled_kernel, dim3(grid_for(L.n1)), dim3(256), 0, s, L.n1, (const float *)W1,
+                           (float)best_a, d1, W1);
+        hipLaunchKernelGGL(add_scaled_kernel, dim3(grid_for(L.n2)), dim3(256), 0, s, L.n2, (const float *)W2,
+                           (float)best_a, d2, W2);
+        HIP_TRY(hipGetLastError());
+    }
+    result->alpha = (float)best_a;
+    result->loss = (float)best_e;
+    result->loss0 = (float)e0;
+    result->bracket_lo = (float)lo;
+    result->bracket_hi = (float)hi;
+    result->error_evaluations = n_err;
+    result->gradient_evaluations = n_grad;
+    return ULSNN_OK;
 }
 
 int ulsnn_mlp_grad_describe_plan(const ulsnn_mlp_desc *desc, int batch, char *buf, size_t buf_bytes)

@@ -128,6 +128,44 @@ def test_sgemm_planned_argument_errors_and_plan_description():
     assert L.ulsnn_sgemm_describe_plan(b"N", b"N", 8, 8, 8, None, 8) == E_NULL
 
 
+def test_optimiser_step_argument_errors():
+    L = ulsnn.load()
+    p, ws = C.c_void_p(0x1000), C.c_void_p(0x2000)
+    n = ulsnn.VEC_WORKSPACE_BYTES
+    assert L.ulsnn_dot(-1, p, p, p, ws, n, None) == E_DIM
+    assert L.ulsnn_dot(8, None, p, p, ws, n, None) == E_NULL
+    assert L.ulsnn_dot(8, p, p, None, ws, n, None) == E_NULL
+    assert L.ulsnn_dot(8, p, p, p, None, n, None) == E_WS
+    assert L.ulsnn_dot(8, p, p, p, ws, n - 1, None) == E_WS
+    assert L.ulsnn_dot(8, p, p, p, C.c_void_p(0x2010), n, None) == E_WS
+    assert L.ulsnn_axpy(-1, 1.0, p, p, None) == E_DIM
+    assert L.ulsnn_axpy(0, 1.0, None, None, None) == OK
+    assert L.ulsnn_axpy(8, 1.0, None, p, None) == E_NULL
+    assert L.ulsnn_cg_direction(8, None, p, p, p, ws, n, None) == E_NULL
+    assert L.ulsnn_cg_direction(8, p, p, None, p, ws, n, None) == E_NULL
+    assert L.ulsnn_cg_direction(8, p, p, p, p, ws, 100, None) == E_WS
+    assert L.ulsnn_cg_direction(-2, p, p, p, p, ws, n, None) == E_DIM
+    # line search
+    res = ulsnn.LineSearchResult()
+    f = lambda d, batch=8, bracket=4, alpha0=0.1, k=5, r=res: L.ulsnn_mlp_line_search(
+        C.byref(d), p, p, p, p, p, p, batch, bracket, alpha0, k, C.byref(r) if r is not None else None)
+    assert f(_desc(), r=None) == E_NULL
+    assert f(_desc(), batch=0) == E_DIM
+    assert f(_desc(), bracket=0) == E_DIM
+    assert f(_desc(), alpha0=0.0) == E_DIM
+    assert f(_desc(), alpha0=float("inf")) == E_DIM
+    assert f(_desc(), k=-1) == E_DIM
+    assert f(_desc(), k=61) == E_DIM
+    assert f(_desc(operand_dtype=1)) == E_UNSUP
+    assert f(_desc(b1=0x1000, b2=0x1000, db1=0x1000, db2=0x1000)) == E_UNSUP
+    assert f(_desc()) == E_WS
+    need = ulsnn.mlp_line_search_workspace_bytes(400, 480, 3203, 8)
+    assert need > ulsnn.mlp_grad_workspace_bytes(400, 480, 3203, 8) + 2 * 4 * (400 * 480 + 480 * 3203)
+    assert f(_desc(workspace=0x1000, workspace_bytes=need - 1)) == E_WS
+    assert L.ulsnn_mlp_line_search(C.byref(_desc(workspace=0x1000, workspace_bytes=need)), p, p, None, p, p, p, 8, 4,
+                                   0.1, 5, C.byref(res)) == E_NULL
+
+
 def test_loss_only_and_mse_argument_errors():
     L = ulsnn.load()
     p, z = C.c_void_p(0x1000), C.c_void_p(0)
