@@ -47,6 +47,8 @@ def parse():
     ap.add_argument("--sgemm-sizes", type=int, nargs="*", default=[256, 1024, 4096, 8192])
     ap.add_argument("--no-bf16", action="store_true", help="skip the bf16-operand workload (batch 65536)")
     ap.add_argument("--no-large-batch", action="store_true", help="skip the fp32 batch-262144 chunk measurement")
+    ap.add_argument("--epoch", action="store_true",
+                    help="also time the whole 9,000,000-pattern epoch (14.4 GB of patterns generated on the GPU)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (reference for HBM byte counters)")
     return ap.parse_args()
@@ -190,6 +192,48 @@ def main():
         r["workload"] = "same net, fp32, one 262144-pattern chunk of the 9,000,000-pattern epoch"
         result["large_batch"] = r
         del Xl, yl
+    # the small case (BASELINE configs[0]): 64-32-10 with biases, batch 256 -- launch-latency bound
+    sm = si.MLP_SMALL
+    sW1, sW2, sb1, sb2 = (t.to(dev) for t in si.mlp_weights(sm, 0))
+    sX, sy = si.mlp_patterns(sm, 0, 0, 256, device=dev)
+    sws = torch.empty(ulsnn.mlp_grad_workspace_bytes(sm.n_in, sm.n_hid, sm.n_out, 256), dtype=torch.uint8, device=dev)
+    sout = ulsnn.MlpGradResult(torch.empty_like(sW1), torch.empty_like(sW2), torch.empty(1, device=dev),
+                               torch.empty_like(sb1), torch.empty_like(sb2))
+    for _ in range(10):
+        ulsnn.mlp_grad(sW1, sW2, sX, sy, sb1, sb2, out=sout, workspace=sws)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(200):
+        ulsnn.mlp_grad(sW1, sW2, sX, sy, sb1, sb2, out=sout, workspace=sws)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t1) / 200
+    result["small_net"] = {"workload": "64-32-10 with biases, batch 256 (launch-latency bound: ten launches)",
+                           "us_per_call": round(sec * 1e6, 2), "patterns_per_s": round(256 / sec, 1),
+                           "gflops": round(ulsnn.mlp_grad_flops(sm.n_in, sm.n_hid, sm.n_out, 256) / sec / 1e9, 2)}
+    if args.epoch:
+        # the epoch workload (BASELINE configs[3]): 9,000,000 patterns resident in HBM, chunks of 262144 summed
+        n_ep, chunk = 9_000_000, 262144
+        Xe = torch.empty(n_ep, shape.n_in, device=dev)
+        ye = torch.empty(n_ep, dtype=torch.int32, device=dev)
+        for p0 in range(0, n_ep, chunk):
+            rows = min(chunk, n_ep - p0)
+            Xe[p0:p0 + rows], ye[p0:p0 + rows] = si.mlp_patterns(shape, SEED, p0, rows, device=dev)
+        wse = torch.empty(ulsnn.mlp_grad_workspace_bytes(shape.n_in, shape.n_hid, shape.n_out, chunk),
+                          dtype=torch.uint8, device=dev)
+        ulsnn.mlp_grad_epoch(W1, W2, Xe[:2 * chunk], ye[:2 * chunk], chunk, out=out, workspace=wse)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ulsnn.mlp_grad_epoch(W1, W2, Xe, ye, chunk, out=out, workspace=wse)
+        torch.cuda.synchronize()
+        sec = time.perf_counter() - t1
+        fl = ulsnn.mlp_grad_flops(shape.n_in, shape.n_hid, shape.n_out, n_ep)
+        result["epoch"] = {"workload": "same net, fp32, 9,000,000 patterns resident in HBM (14.4 GB), 34 chunks of "
+                                       "262144 + one of 87104, gradients and loss summed",
+                           "patterns": n_ep, "seconds": round(sec, 4), "gflops": round(fl / sec / 1e9, 1),
+                           "patterns_per_s": round(n_ep / sec, 1),
+                           "frac_of_fp32_mfma_peak": round(fl / sec / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4),
+                           "loss_per_pattern": round(out.loss.item() / n_ep, 6)}
+        del Xe, ye, wse
     if not args.no_bf16:
         # bf16-operand workload (BASELINE configs[4]): X, W stored bf16, batch 65536, fp32 accumulation
         Xb, yb = si.mlp_patterns(shape, SEED, 0, 65536, device=dev)

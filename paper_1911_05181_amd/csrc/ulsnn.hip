@@ -234,12 +234,17 @@ hipError_t launch_reduce(int splits, int epi, const GemmArgs &a, const float *pa
 
 using T16_128 = Tile16<128, 128, 2, 2, 3>;   // 256 threads, 3 workgroups / CU
 using T16_64 = Tile16<64, 64, 2, 2, 8>;      // 256 threads, 8 workgroups / CU
+// Wavefront sub-tile 128 x 64: a third fewer LDS bytes per matrix instruction than 64 x 64 (the 128x128 shape is
+// bound by LDS reads).  Two workgroups per CU, so the epilogue's stores are poorly hidden: long-k products only.
+using T16_256 = Tile16<256, 128, 2, 2, 2>;
 
-enum Cfg16Id { CFG16_128 = 0, CFG16_64, CFG16_COUNT };
+enum Cfg16Id { CFG16_128 = 0, CFG16_64, CFG16_256, CFG16_COUNT };
+constexpr int CFG16_256_MIN_K = 1024;
 
 constexpr CfgInfo CFG16_INFO[CFG16_COUNT] = {
     {128, 128, 32, 256, 3, 1.00, "bf16 128x128"},
     {64, 64, 32, 256, 8, 0.70, "bf16 64x64"},
+    {256, 128, 32, 256, 2, 1.30, "bf16 256x128"},
 };
 constexpr double BF16_SUSTAINED_FLOPS = 800.0e12;   // what the 128x128 bf16 tile sustains on large problems
 
@@ -256,6 +261,7 @@ Gemm16Plan plan_gemm16(int m, int n, int k, bool a_kc, bool b_kc, bool allow_spl
     best.est_us = 1e30;
     for (int ci = 0; ci < CFG16_COUNT; ++ci) {
         const CfgInfo &c = CFG16_INFO[ci];
+        if (ci == CFG16_256 && k < CFG16_256_MIN_K) continue;
         int max_splits = allow_split ? std::max(1, std::min(64, k / (8 * c.bk))) : 1;
         if ((size_t)m * n > 0) max_splits = (int)std::min<size_t>(max_splits, std::max<size_t>(1, max_partial_floats / ((size_t)m * n)));
         for (int s = 1; s <= max_splits; ++s) {
@@ -303,7 +309,7 @@ hipError_t launch_gemm16(const Gemm16Plan &p, bool a_kc, bool b_kc, int epi, Gem
         if (epi == EPI_AXPBY && !a_kc && !b_kc) return launch16_one<Cfg, false, false, EPI_AXPBY>(a, p.splits, s);
         return hipErrorInvalidValue;
     };
-    return p.cfg == CFG16_128 ? go(T16_128{}) : go(T16_64{});
+    return p.cfg == CFG16_128 ? go(T16_128{}) : p.cfg == CFG16_256 ? go(T16_256{}) : go(T16_64{});
 }
 
 // ---------------------------------------------------------------------------------------------------------
