@@ -180,3 +180,42 @@ def test_workspace_too_small_is_refused():
     with pytest.raises(ulsnn.UlsnnError) as e:
         _gpu_grad(*p, workspace=ws)
     assert e.value.status == 5
+
+
+def test_full_size_epoch_9_million_patterns():
+    """The epoch workload at its full size: 9,000,000 patterns resident on the GPU, chunks of 262144.
+    The oracle cannot run 90 TFLOP, so parity is pinned by (i) additivity: the epoch gradient equals the float64
+    sum of the 35 per-chunk gradients computed by separate calls, and (ii) the oracle on one 4096-pattern prefix
+    of a chunk chosen in the middle of the epoch, regenerated from the counter-based generator."""
+    shape, n, chunk = si.MLP_JOCR, 9_000_000, 262144
+    W1, W2, _, _ = si.mlp_weights(shape, 2, device=DEV)
+    X = torch.empty(n, shape.n_in, device=DEV)
+    y = torch.empty(n, dtype=torch.int32, device=DEV)
+    for p0 in range(0, n, chunk):
+        rows = min(chunk, n - p0)
+        X[p0:p0 + rows], y[p0:p0 + rows] = si.mlp_patterns(shape, 2, p0, rows, device=DEV)
+    ws = torch.empty(ulsnn.mlp_grad_workspace_bytes(shape.n_in, shape.n_hid, shape.n_out, chunk), dtype=torch.uint8,
+                     device=DEV)
+    res = ulsnn.mlp_grad_epoch(W1, W2, X, y, chunk, workspace=ws)
+    torch.cuda.synchronize()
+    s1 = torch.zeros(W1.shape, dtype=torch.float64, device=DEV)
+    s2 = torch.zeros(W2.shape, dtype=torch.float64, device=DEV)
+    sl = 0.0
+    part = ulsnn.MlpGradResult(torch.empty_like(W1), torch.empty_like(W2), torch.empty(1, device=DEV))
+    for p0 in range(0, n, chunk):
+        rows = min(chunk, n - p0)
+        ulsnn.mlp_grad(W1, W2, X[p0:p0 + rows], y[p0:p0 + rows], out=part, workspace=ws)
+        s1 += part.dW1.double()
+        s2 += part.dW2.double()
+        sl += part.loss.item()
+    e1 = ((res.dW1.double() - s1).norm() / s1.norm()).item()
+    e2 = ((res.dW2.double() - s2).norm() / s2.norm()).item()
+    print(f"epoch 9e6 vs float64 sum of 35 chunk gradients: dW1 {e1:.2e} dW2 {e2:.2e} loss {abs(res.loss.item() - sl) / sl:.2e}")
+    assert e1 < 1e-5 and e2 < 1e-5 and abs(res.loss.item() - sl) <= 1e-5 * sl
+    # one chunk from the middle of the epoch against the oracle (first 4096 patterns of chunk 17)
+    p0 = 17 * chunk
+    Xc, yc = si.mlp_patterns(shape, 2, p0, 4096)                       # regenerated on the CPU
+    assert torch.equal(Xc, X[p0:p0 + 4096].cpu()) and torch.equal(yc, y[p0:p0 + 4096].cpu())
+    got = ulsnn.mlp_grad(W1, W2, X[p0:p0 + 4096], y[p0:p0 + 4096])
+    torch.cuda.synchronize()
+    _compare(got, _oracle_grad(W1.cpu(), W2.cpu(), None, None, Xc, yc), "chunk 17 prefix of the epoch")
