@@ -228,6 +228,73 @@ hipError_t launch_reduce(int splits, int epi, const GemmArgs &a, const float *pa
     return hipGetLastError();
 }
 
+// Work that rides along with the launch of the dW1 product when the batch is small: the reduction of the dW2
+// partial products (HBM-bound, independent of dW1) fills compute units the short dW1 product leaves idle, and the
+// sum of the row losses needs no launch of its own.
+struct TailWork {
+    const float *partial;    // dW2 split-k partials, dense M x N each, `stride` elements apart
+    size_t stride;
+    int splits;
+    float *out;              // dW2
+    int M, N, ldc;
+    float beta;
+    int reduce_blocks;       // workgroups that share the reduction
+    const float *row_loss;   // one loss per pattern
+    long long rows;
+    float *loss;
+    float loss_beta;
+};
+
+// Workgroups [0, n_gemm): split-k partial products of g (TN);  [n_gemm, n_gemm + reduce_blocks): dW2 reduction;
+// the last workgroup: loss = loss_beta*loss + sum of the row losses (double, fixed order).
+template <class Cfg>
+__global__ __launch_bounds__(256, Cfg::WAVES_PER_SIMD) void dw1_with_tail_kernel(const GemmArgs g, const int n_gemm,
+                                                                                 const TailWork t)
+{
+    static_assert(Cfg::THREADS == 256, "tail work is written for 256 threads");
+    __shared__ __attribute__((aligned(16))) float lds[gemm_lds_floats<Cfg, false, false>()];
+    const int id = blockIdx.x;
+    if (id < n_gemm) {
+        const int tiles = g.tiles_m * g.tiles_n;
+        gemm_tile<Cfg, false, false, EPI_PARTIAL>(g, id % tiles, id / tiles, lds, id);
+    } else if (id < n_gemm + t.reduce_blocks) {
+        const size_t total = (size_t)t.M * t.N;
+        for (size_t idx = (size_t)(id - n_gemm) * 256 + threadIdx.x; idx < total; idx += (size_t)t.reduce_blocks * 256) {
+            float sum = 0.f;
+            for (int z = 0; z < t.splits; ++z) sum += t.partial[(size_t)z * t.stride + idx];   // fixed order
+            float *dst = t.out + (idx / t.N) * (size_t)t.ldc + (idx % t.N);
+            *dst = t.beta != 0.f ? sum + t.beta * *dst : sum;
+        }
+    } else {
+        double *red = reinterpret_cast<double *>(lds);
+        double sum = 0.0;
+        for (long long r = threadIdx.x; r < t.rows; r += 256) sum += (double)t.row_loss[r];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sum;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            *t.loss = (t.loss_beta != 0.f ? t.loss_beta * *t.loss : 0.f) + (float)(red[0] + red[1] + red[2] + red[3]);
+    }
+}
+
+hipError_t launch_dw1_with_tail(const GemmPlan &p, GemmArgs a, const TailWork &t, hipStream_t s)
+{
+    a.tiles_m = p.tiles_m;
+    a.tiles_n = p.tiles_n;
+    a.kchunk = p.kchunk;
+    const int n_gemm = p.tiles_m * p.tiles_n * p.splits;
+    const dim3 grid((unsigned)(n_gemm + t.reduce_blocks + 1));
+    switch (p.cfg) {
+        case CFG_128: hipLaunchKernelGGL(dw1_with_tail_kernel<Cfg128>, grid, dim3(256), 0, s, a, n_gemm, t); break;
+        case CFG_128x64: hipLaunchKernelGGL(dw1_with_tail_kernel<Cfg128x64>, grid, dim3(256), 0, s, a, n_gemm, t); break;
+        case CFG_64x128: hipLaunchKernelGGL(dw1_with_tail_kernel<Cfg64x128>, grid, dim3(256), 0, s, a, n_gemm, t); break;
+        case CFG_64: hipLaunchKernelGGL(dw1_with_tail_kernel<Cfg64>, grid, dim3(256), 0, s, a, n_gemm, t); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // bf16-operand GEMM dispatch (fp32 accumulation): two tile shapes, same cost model with the measured bf16 rate
 // ---------------------------------------------------------------------------------------------------------
@@ -515,7 +582,13 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, con
                 hipLaunchKernelGGL((softmax_ce_long_kernel<256, false, false>), dim3(rows), dim3(256), 0, s, Z, L.ldz,
                                    n_out, ys, row_loss, (u16 *)nullptr, 0);
         }
-        hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, row_loss, (long long)rows, loss, beta);
+        // Small batches: the dW2 reduction and the loss sum ride along with the dW1 product's launch (whose
+        // partials then go to the hidden-delta region, free by then).
+        const bool fuse_tail = task.backward && P.g3.splits > 1 && P.g5.splits > 1 &&
+                               (CFGS_256_THREADS >> P.g5.cfg & 1) != 0 &&
+                               (size_t)P.g5.splits * n_in * n_hid <= L.floats_pb;
+        if (!fuse_tail)
+            hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, row_loss, (long long)rows, loss, beta);
         HIP_TRY(hipGetLastError());
         MARK(3);
         if (!task.backward) {
@@ -536,7 +609,7 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, con
             HIP_TRY(launch_pair_partial(P.g4, p4, P.g3, p3, s));
             MARK(4);
             HIP_TRY(launch_reduce(P.g4.splits, EPI_TANHGRAD, a4, part_b, s));
-            HIP_TRY(launch_reduce(P.g3.splits, EPI_AXPBY, a3, part_a, s));
+            if (!fuse_tail) HIP_TRY(launch_reduce(P.g3.splits, EPI_AXPBY, a3, part_a, s));
         } else {
             GemmArgs p3 = a3, p4 = a4;
             if (P.g4.splits > 1) { p4.C = part_b; p4.partial_stride = (size_t)a4.M * a4.N; }
@@ -545,7 +618,7 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, con
             HIP_TRY(launch_gemm(P.g3, false, false, P.g3.splits > 1 ? EPI_PARTIAL : EPI_AXPBY, p3, s));
             MARK(4);
             if (P.g4.splits > 1) HIP_TRY(launch_reduce(P.g4.splits, EPI_TANHGRAD, a4, part_b, s));
-            if (P.g3.splits > 1) HIP_TRY(launch_reduce(P.g3.splits, EPI_AXPBY, a3, part_a, s));
+            if (P.g3.splits > 1 && !fuse_tail) HIP_TRY(launch_reduce(P.g3.splits, EPI_AXPBY, a3, part_a, s));
         }
         MARK(5);
 
@@ -553,7 +626,18 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, con
         a = GemmArgs{};
         a.A = Xs; a.lda = n_in; a.B = dA1; a.ldb = L.ldh; a.C = dW1; a.ldc = n_hid;
         a.M = n_in; a.N = n_hid; a.K = rows; a.alpha = 1.f; a.beta = beta;
-        if (P.g5.splits > 1) {
+        if (fuse_tail) {
+            GemmArgs p5 = a;
+            p5.C = part_b; p5.partial_stride = (size_t)a.M * a.N;
+            TailWork t{};
+            t.partial = part_a; t.stride = (size_t)a3.M * a3.N; t.splits = P.g3.splits;
+            t.out = dW2; t.M = a3.M; t.N = a3.N; t.ldc = a3.ldc; t.beta = beta;
+            t.reduce_blocks = (int)grid_for(t.stride);
+            t.row_loss = row_loss; t.rows = rows; t.loss = loss; t.loss_beta = beta;
+            HIP_TRY(launch_dw1_with_tail(P.g5, p5, t, s));
+            MARK(6);
+            HIP_TRY(launch_reduce(P.g5.splits, EPI_AXPBY, a, part_b, s));
+        } else if (P.g5.splits > 1) {
             GemmArgs p5 = a;
             p5.C = part_a; p5.partial_stride = (size_t)a.M * a.N;
             HIP_TRY(launch_gemm(P.g5, false, false, EPI_PARTIAL, p5, s));
