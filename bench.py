@@ -55,7 +55,10 @@ def parse():
 
 
 def bench_sgemm(ulsnn, si, torch, sizes):
-    """alpha = 1, beta = 0.5, entries uniform[-1,1], seed 1; NN, NT, TN; median of event-timed calls."""
+    """alpha = 1, beta = 0.5, entries uniform[-1,1], seed 1; NN, NT, TN.  `ms` = one call's share of a run of
+    back-to-back calls bracketed by two events (throughput; what `gflops` is computed from); `ms_single` = median
+    of calls timed one at a time with an event on each side and a synchronisation in between (latency: adds the
+    event overhead and an idle gap, which dominates below 1024)."""
     out = {}
     for size in sizes:
         m = n = k = size
@@ -75,9 +78,16 @@ def bench_sgemm(ulsnn, si, torch, sizes):
                 e1.synchronize()
                 times.append(e0.elapsed_time(e1))
             times.sort()
-            med = times[len(times) // 2]
-            gf = ulsnn.sgemm_flops(m, n, k) / (med * 1e-3) / 1e9
-            out[f"{ta}{tb}_{size}"] = {"ms": round(med, 4), "gflops": round(gf, 1),
+            single = times[len(times) // 2]
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                ulsnn.sgemm(ta, tb, m, n, k, 1.0, A, k, B, n, 0.5, Cm, n)
+            e1.record()
+            e1.synchronize()
+            per_call = e0.elapsed_time(e1) / reps
+            gf = ulsnn.sgemm_flops(m, n, k) / (per_call * 1e-3) / 1e9
+            out[f"{ta}{tb}_{size}"] = {"ms": round(per_call, 4), "ms_single": round(single, 4), "gflops": round(gf, 1),
                                       "frac_of_peak": round(gf / (PEAK_FP32_MFMA_TFLOPS * 1e3), 4)}
         del A, B, C0
     return out

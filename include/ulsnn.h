@@ -240,7 +240,7 @@ int ulsnn_mlp_line_search(const ulsnn_mlp_desc *desc, float *W1, float *W2, cons
  * The same operation as ulsnn_sgemm (section 3.1) with the blocking chosen by the caller instead of the built-in
  * planner (for autotuning, and for tests that must reach every tile shape): `tile_shape` is one of
  * ULSNN_TILE_*, `k_splits` >= 1 the number of slices the k range is cut into (slices are rounded up to the k
- * step of 16, so fewer may remain).  With more than one slice the partial products go to `workspace` (device
+ * step of the tile shape, 16 or 64, so fewer may remain).  With more than one slice the partial products go to `workspace` (device
  * memory, 256-byte aligned, at least k_splits*m*n*4 bytes; else ULSNN_ERR_WORKSPACE) and are added in slice
  * order, so results are deterministic.  Argument rules, layout, ownership and error behaviour otherwise as
  * for ulsnn_sgemm.
@@ -251,7 +251,8 @@ int ulsnn_mlp_line_search(const ulsnn_mlp_desc *desc, float *W1, float *W2, cons
 #define ULSNN_TILE_128x64 3
 #define ULSNN_TILE_64x128 4
 #define ULSNN_TILE_64x64 5
-#define ULSNN_TILE_COUNT 6
+#define ULSNN_TILE_64x64_K64 6 /* k step 64 instead of 16: for launches too small to fill the chip */
+#define ULSNN_TILE_COUNT 7
 int ulsnn_sgemm_planned(int tile_shape, int k_splits, char transa, char transb, int m, int n, int k, float alpha,
                         const float *A, int lda, const float *B, int ldb, float beta, float *C, int ldc,
                         void *workspace, size_t workspace_bytes, void *hip_stream);
