@@ -31,7 +31,7 @@ PEAK_FP32_MFMA_TFLOPS = 157.3      # 256 CUs x 256 flop/clk/CU x 2.4 GHz
 # HBM bytes per launch of the dominant kernel (paired backward products, batch 4096): rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB copy (2.000 and 1.000); 275.1 MB read,
 # 56.1 MB written.  Source: profiles/mlp_grad_b4096_hbm_traffic_pmc.md.  Algorithmic: 119.0 MB read, 54.3 MB written.
-PMC_TRAFFIC_BYTES = {"backward_products": 331.2e6}
+PMC_TRAFFIC_BYTES = {"backward_products": 327.5e6}
 METRIC = "fp32 GFLOP/s (% of MFMA FP32 peak); MLP gradient patterns/sec"
 BATCH = 4096
 SEED = 2
@@ -47,6 +47,7 @@ def parse():
     ap.add_argument("--sgemm-sizes", type=int, nargs="*", default=[256, 1024, 4096, 8192])
     ap.add_argument("--no-bf16", action="store_true", help="skip the bf16-operand workload (batch 65536)")
     ap.add_argument("--no-large-batch", action="store_true", help="skip the fp32 batch-262144 chunk measurement")
+    ap.add_argument("--no-small-net", action="store_true", help="skip the 64-32-10 latency measurement")
     ap.add_argument("--epoch", action="store_true",
                     help="also time the whole 9,000,000-pattern epoch (14.4 GB of patterns generated on the GPU)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -202,24 +203,25 @@ def main():
         r["workload"] = "same net, fp32, one 262144-pattern chunk of the 9,000,000-pattern epoch"
         result["large_batch"] = r
         del Xl, yl
-    # the small case (BASELINE configs[0]): 64-32-10 with biases, batch 256 -- launch-latency bound
-    sm = si.MLP_SMALL
-    sW1, sW2, sb1, sb2 = (t.to(dev) for t in si.mlp_weights(sm, 0))
-    sX, sy = si.mlp_patterns(sm, 0, 0, 256, device=dev)
-    sws = torch.empty(ulsnn.mlp_grad_workspace_bytes(sm.n_in, sm.n_hid, sm.n_out, 256), dtype=torch.uint8, device=dev)
-    sout = ulsnn.MlpGradResult(torch.empty_like(sW1), torch.empty_like(sW2), torch.empty(1, device=dev),
-                               torch.empty_like(sb1), torch.empty_like(sb2))
-    for _ in range(10):
-        ulsnn.mlp_grad(sW1, sW2, sX, sy, sb1, sb2, out=sout, workspace=sws)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for _ in range(200):
-        ulsnn.mlp_grad(sW1, sW2, sX, sy, sb1, sb2, out=sout, workspace=sws)
-    torch.cuda.synchronize()
-    sec = (time.perf_counter() - t1) / 200
-    result["small_net"] = {"workload": "64-32-10 with biases, batch 256 (launch-latency bound: ten launches)",
-                           "us_per_call": round(sec * 1e6, 2), "patterns_per_s": round(256 / sec, 1),
-                           "gflops": round(ulsnn.mlp_grad_flops(sm.n_in, sm.n_hid, sm.n_out, 256) / sec / 1e9, 2)}
+    if not args.no_small_net:
+        # the small case (BASELINE configs[0]): 64-32-10 with biases, batch 256 -- launch-latency bound
+        sm = si.MLP_SMALL
+        sW1, sW2, sb1, sb2 = (t.to(dev) for t in si.mlp_weights(sm, 0))
+        sX, sy = si.mlp_patterns(sm, 0, 0, 256, device=dev)
+        sws = torch.empty(ulsnn.mlp_grad_workspace_bytes(sm.n_in, sm.n_hid, sm.n_out, 256), dtype=torch.uint8, device=dev)
+        sout = ulsnn.MlpGradResult(torch.empty_like(sW1), torch.empty_like(sW2), torch.empty(1, device=dev),
+                                   torch.empty_like(sb1), torch.empty_like(sb2))
+        for _ in range(10):
+            ulsnn.mlp_grad(sW1, sW2, sX, sy, sb1, sb2, out=sout, workspace=sws)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(200):
+            ulsnn.mlp_grad(sW1, sW2, sX, sy, sb1, sb2, out=sout, workspace=sws)
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t1) / 200
+        result["small_net"] = {"workload": "64-32-10 with biases, batch 256 (launch-latency bound: ten launches)",
+                               "us_per_call": round(sec * 1e6, 2), "patterns_per_s": round(256 / sec, 1),
+                               "gflops": round(ulsnn.mlp_grad_flops(sm.n_in, sm.n_hid, sm.n_out, 256) / sec / 1e9, 2)}
     if args.epoch:
         # the epoch workload (BASELINE configs[3]): 9,000,000 patterns resident in HBM, chunks of 262144 summed
         n_ep, chunk = 9_000_000, 262144

@@ -596,7 +596,7 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, con
         }
         // Small batches: the dW2 reduction and the loss sum ride along with the dW1 product's launch (whose
         // partials then go to the hidden-delta region, free by then).
-        const bool fuse_tail = task.backward && P.g3.splits > 1 && P.g5.splits > 1 &&
+        const bool fuse_tail = task.backward && P.paired && P.g5.splits > 1 &&
                                (CFGS_256_THREADS >> P.g5.cfg & 1) != 0 &&
                                (size_t)P.g5.splits * n_in * n_hid <= L.floats_pb;
         if (!fuse_tail)
