@@ -122,17 +122,20 @@ __device__ __forceinline__ void panel16_store(u16 *lds, const u16x8 (&reg)[NV], 
     }
 }
 
-// Unchecked 16-byte fetch for full k steps of aligned operands (see FastFetch in gemm.hpp for the edge rules).
+// Unchecked 16-byte fetch for full k steps of aligned operands (pointer and leading dimension multiples of 8
+// elements).  Offsets are fixed per thread as in FastFetch (gemm.hpp).  A vector that lies wholly beyond the
+// matrix edge is redirected to a valid address (row clamped for KC, first column of the tile for MC).  An MC
+// vector that straddles the edge needs no guard: it starts at a multiple of 8 below the width N and the row
+// stride is a multiple of 8 not smaller than N, so its 8 elements stay inside the row; the elements beyond N
+// only reach accumulators that are never stored.
 template <bool KC, int R, int THREADS, int NV>
 struct FastFetch16 {
     unsigned off[NV];
-    unsigned edge;
     int valid;
 
     __device__ __forceinline__ void init(int ld, int r0, int rmax, int tid)
     {
         constexpr int TOTAL = R * 32 / 8;
-        edge = 0;
         valid = rmax - r0;
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
@@ -146,12 +149,7 @@ struct FastFetch16 {
             } else {
                 const int krow = f / (R / 8);
                 int rq = (f % (R / 8)) * 8;
-                if (rq >= valid) {
-                    rq = 0;
-                    if (valid < 8) edge |= 1u << v;   // first vector of the tile straddles too: load nothing
-                } else if (rq + 7 >= valid) {
-                    edge |= 1u << v;
-                }
+                if (rq >= valid) rq = 0;
                 off[v] = (unsigned)krow * (unsigned)ld + (unsigned)rq;
             }
         }
@@ -159,20 +157,9 @@ struct FastFetch16 {
 
     __device__ __forceinline__ void fetch(u16x8 (&reg)[NV], const u16 *__restrict__ base, int tid) const
     {
+        (void)tid;
 #pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            const u16 *src = base + off[v];
-            if (KC || !(edge >> v & 1)) {
-                reg[v] = load8_aligned(src);
-            } else {
-                const int rq = ((tid + v * THREADS) % (R / 8)) * 8;
-                u16x8 val = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (rq + e < valid) val[e] = src[e];
-                reg[v] = val;
-            }
-        }
+        for (int v = 0; v < NV; ++v) reg[v] = load8_aligned(base + off[v]);
     }
 };
 
