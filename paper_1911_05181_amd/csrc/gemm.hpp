@@ -183,10 +183,18 @@ __device__ __forceinline__ void grouped_tile(int lid, int tiles_m, int tiles_n, 
     tn = (lid % group) / gsz;
 }
 
-// Map the hardware workgroup id of a plain launch to a tile: XCD-contiguous, then grouped.
-__device__ __forceinline__ void tile_of_workgroup(int pid, int tiles_m, int tiles_n, int &tm, int &tn)
+// Map the hardware workgroup id `hw` of a launch of tiles x splits workgroups (x fastest) to (tile, k split).
+// The XCD-contiguous positions run over the WHOLE tiles x splits range, split-major: one XCD then works on a
+// block of neighbouring tiles of ONE k slice at a time, so the operand panels those tiles share are fetched into
+// that XCD's L2 once.  (Giving every XCD a share of every split made each panel a guest in several L2s: the
+// hidden-delta product at 4096 patterns read 132 MB for 59 MB of operands.)  Within a split, tiles are grouped.
+__device__ __forceinline__ void work_of_workgroup(int hw, int tiles_m, int tiles_n, int splits, int &tm, int &tn,
+                                                  int &z)
 {
-    grouped_tile(xcd_contiguous(pid, tiles_m * tiles_n), tiles_m, tiles_n, tm, tn);
+    const int tiles = tiles_m * tiles_n;
+    const int pos = xcd_contiguous(hw, tiles * splits);
+    z = pos / tiles;
+    grouped_tile(pos - z * tiles, tiles_m, tiles_n, tm, tn);
 }
 
 __device__ __forceinline__ float tanh_f32(float x)
@@ -511,13 +519,13 @@ __device__ __forceinline__ void gemm_segment(const GemmArgs &g, const int tile_m
 #endif
 }
 
-// The work of one workgroup of a plain launch: tile number `pid` (before the XCD / group remapping), k split `z`.
+// The work of one workgroup: `hw` is its position in the launch order of this problem's tiles x splits workgroups.
 template <class Cfg, bool A_KC, bool B_KC, int EPI>
-__device__ __forceinline__ void gemm_tile(const GemmArgs &g, const int pid, const int z, float *lds,
+__device__ __forceinline__ void gemm_tile(const GemmArgs &g, const int hw, const int splits, float *lds,
                                           const int wg_linear)
 {
-    int tile_m, tile_n;
-    tile_of_workgroup(pid, g.tiles_m, g.tiles_n, tile_m, tile_n);
+    int tile_m, tile_n, z;
+    work_of_workgroup(hw, g.tiles_m, g.tiles_n, splits, tile_m, tile_n, z);
     const int kbeg = z * g.kchunk;
     const int kend = (kbeg + g.kchunk < g.K) ? kbeg + g.kchunk : g.K;
     float *Cout = g.C;
@@ -534,7 +542,8 @@ template <class Cfg, bool A_KC, bool B_KC, int EPI>
 __global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm_kernel(const GemmArgs g)
 {
     __shared__ __attribute__((aligned(16))) float lds[gemm_lds_floats<Cfg, A_KC, B_KC>()];
-    gemm_tile<Cfg, A_KC, B_KC, EPI>(g, blockIdx.x, blockIdx.y, lds, blockIdx.y * gridDim.x + blockIdx.x);
+    const int hw = blockIdx.y * gridDim.x + blockIdx.x;
+    gemm_tile<Cfg, A_KC, B_KC, EPI>(g, hw, gridDim.y, lds, hw);
 }
 
 // Two independent GEMMs in one launch (1-D grid): workgroups [0, n1) work on g1, the rest on g2.  The second
@@ -550,11 +559,10 @@ void gemm_pair_kernel(const GemmArgs g1, const GemmArgs g2, const int n1)
     __shared__ __attribute__((aligned(16))) float lds[L1 > L2 ? L1 : L2];
     const int id = blockIdx.x;
     if (id < n1) {
-        const int t = g1.tiles_m * g1.tiles_n;
-        gemm_tile<Cfg1, A_KC1, B_KC1, EPI1>(g1, id % t, id / t, lds, id);
+        gemm_tile<Cfg1, A_KC1, B_KC1, EPI1>(g1, id, n1 / (g1.tiles_m * g1.tiles_n), lds, id);
     } else {
-        const int t = g2.tiles_m * g2.tiles_n, r = id - n1;
-        gemm_tile<Cfg2, A_KC2, B_KC2, EPI2>(g2, r % t, r / t, lds, id);
+        const int n2 = gridDim.x - n1;
+        gemm_tile<Cfg2, A_KC2, B_KC2, EPI2>(g2, id - n1, n2 / (g2.tiles_m * g2.tiles_n), lds, id);
     }
 }
 

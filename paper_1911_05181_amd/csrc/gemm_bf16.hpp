@@ -194,7 +194,7 @@ constexpr int gemm16_lds_elems()
 
 // OUT_BF16: C is bf16 (EPI_BIAS_TANH, EPI_TANHGRAD) else fp32.
 template <class Cfg, bool A_KC, bool B_KC, int EPI>
-__device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int pid, const int z, u16 *lds)
+__device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, const int splits, u16 *lds)
 {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = 32, THREADS = Cfg::THREADS;
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
@@ -213,8 +213,8 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int pid, 
     const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
     const int wrow = wm * Cfg::WTM, wcol = wn * Cfg::WTN;
 
-    int tile_m, tile_n;
-    tile_of_workgroup(pid, g.tiles_m, g.tiles_n, tile_m, tile_n);
+    int tile_m, tile_n, z;
+    work_of_workgroup(hw, g.tiles_m, g.tiles_n, splits, tile_m, tile_n, z);
     const int i0 = tile_m * BM, j0 = tile_n * BN;
     const int kbeg = z * g.kchunk;
     const int kend = (kbeg + g.kchunk < g.K) ? kbeg + g.kchunk : g.K;
@@ -349,7 +349,7 @@ template <class Cfg, bool A_KC, bool B_KC, int EPI>
 __global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm16_kernel(const Gemm16Args g)
 {
     __shared__ __attribute__((aligned(16))) u16 lds[gemm16_lds_elems<Cfg, A_KC, B_KC>()];
-    gemm16_tile<Cfg, A_KC, B_KC, EPI>(g, blockIdx.x, blockIdx.y, lds);
+    gemm16_tile<Cfg, A_KC, B_KC, EPI>(g, blockIdx.y * gridDim.x + blockIdx.x, gridDim.y, lds);
 }
 
 }  // namespace ulsnn

@@ -267,8 +267,7 @@ __global__ __launch_bounds__(256, Cfg::WAVES_PER_SIMD) void dw1_with_tail_kernel
     __shared__ __attribute__((aligned(16))) float lds[gemm_lds_floats<Cfg, false, false>()];
     const int id = blockIdx.x;
     if (id < n_gemm) {
-        const int tiles = g.tiles_m * g.tiles_n;
-        gemm_tile<Cfg, false, false, EPI_PARTIAL>(g, id % tiles, id / tiles, lds, id);
+        gemm_tile<Cfg, false, false, EPI_PARTIAL>(g, id, n_gemm / (g.tiles_m * g.tiles_n), lds, id);
     } else if (id < n_gemm + t.reduce_blocks) {
         const size_t total = (size_t)t.M * t.N;
         for (size_t idx = (size_t)(id - n_gemm) * 256 + threadIdx.x; idx < total; idx += (size_t)t.reduce_blocks * 256) {
