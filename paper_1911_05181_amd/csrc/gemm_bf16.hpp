@@ -53,9 +53,13 @@ struct Gemm16Args {
     int aligned;           // 1: A and B rows are 16-byte aligned (fast vector fetch allowed)
 };
 
-template <int BM_, int BN_, int WM_, int WN_, int WAVES_PER_SIMD_ = 1>
+// PREFETCH_ = k steps kept in flight in registers.  A bf16 step is eight times shorter on the matrix cores than an
+// fp32 one, so a single step of products does not cover the latency of the next step's global loads.
+template <int BM_, int BN_, int WM_, int WN_, int WAVES_PER_SIMD_ = 1, int PREFETCH_ = 1>
 struct Tile16 {
     static constexpr int BM = BM_, BN = BN_, BK = 32, WM = WM_, WN = WN_, WAVES_PER_SIMD = WAVES_PER_SIMD_;
+    static constexpr int PREFETCH = PREFETCH_;
+    static_assert(PREFETCH_ >= 1, "prefetch depth");
     static constexpr int THREADS = WM * WN * 64;
     static constexpr int WTM = BM / WM, WTN = BN / WN;
     static constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -66,7 +70,9 @@ struct Tile16 {
 // alignment of every read
 template <bool KC, int R>
 struct Panel16 {
-    static constexpr int LD = KC ? (32 + 8) : (R + 8);
+    // KC: rows of 32 + 8 elements.  MC: k rows 8 banks (32 B) apart modulo the 32 banks, so the four k rows a
+    // 16-lane group of the transpose read touches cover all banks once (R + 8 gave 2-way conflicts).
+    static constexpr int LD = KC ? (32 + 8) : (R + 16);
     static constexpr int SIZE = KC ? R * LD : 32 * LD;
 };
 
@@ -239,22 +245,37 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
     const size_t step_a = A_KC ? (size_t)BK : (size_t)BK * g.lda;
     const size_t step_b = B_KC ? (size_t)BK : (size_t)BK * g.ldb;
 
-    u16x8 ra[NVA], rb[NVB];
+    constexpr int D = Cfg::PREFETCH;
+    // Register slots of the fetch pipeline: while step kb is multiplied out of LDS, the loads of steps
+    // kb+1 .. kb+D are in flight; step s lives in slot s % D (the loops below are unrolled so that slot numbers are
+    // compile-time constants).
+    u16x8 ra[D][NVA], rb[D][NVB];
 #pragma unroll
-    for (int v = 0; v < NVA; ++v) ra[v] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    for (int u = 0; u < D; ++u) {
 #pragma unroll
-    for (int v = 0; v < NVB; ++v) rb[v] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        for (int v = 0; v < NVA; ++v) ra[u][v] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int v = 0; v < NVB; ++v) rb[u][v] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    }
 
+    const u16 *na = pa, *nb = pb;   // where the next unchecked fetch reads
     if (nkb > 0) {
         if (nfull > 0) {
-            fa.fetch(ra, pa, tid);
-            fb.fetch(rb, pb, tid);
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                if (u < nfull) {
+                    fa.fetch(ra[u], na, tid);
+                    fb.fetch(rb[u], nb, tid);
+                    na += step_a;
+                    nb += step_b;
+                }
+            }
         } else {
-            panel16_fetch_checked<A_KC, BM, THREADS, NVA>(ra, g.A, g.lda, i0, g.M, kbeg, kend, tid);
-            panel16_fetch_checked<B_KC, BN, THREADS, NVB>(rb, g.B, g.ldb, j0, g.N, kbeg, kend, tid);
+            panel16_fetch_checked<A_KC, BM, THREADS, NVA>(ra[0], g.A, g.lda, i0, g.M, kbeg, kend, tid);
+            panel16_fetch_checked<B_KC, BN, THREADS, NVB>(rb[0], g.B, g.ldb, j0, g.N, kbeg, kend, tid);
         }
-        panel16_store<A_KC, BM, THREADS, NVA>(stage_a(0), ra, tid);
-        panel16_store<B_KC, BN, THREADS, NVB>(stage_b(0), rb, tid);
+        panel16_store<A_KC, BM, THREADS, NVA>(stage_a(0), ra[0], tid);
+        panel16_store<B_KC, BN, THREADS, NVB>(stage_b(0), rb[0], tid);
     }
     __syncthreads();
 
@@ -275,30 +296,48 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
         }
     };
 
-    int kb = 0;
-    for (; kb + 1 < nfull; ++kb) {
-        const int cur = kb & 1;
-        pa += step_a;
-        pb += step_b;
-        fa.fetch(ra, pa, tid);
-        fb.fetch(rb, pb, tid);
-        compute(cur);
-        panel16_store<A_KC, BM, THREADS, NVA>(stage_a(cur ^ 1), ra, tid);
-        panel16_store<B_KC, BN, THREADS, NVB>(stage_b(cur ^ 1), rb, tid);
-        __syncthreads();
+    // Full steps 0 .. nfull-1.  On entry to step kb its panels are in LDS stage kb & 1 and slot kb % D is free.
+    for (int base = 0; base < nfull; base += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int kb = base + u;
+            if (kb < nfull) {
+                const int cur = kb & 1, next = kb + 1;
+                const int un = (u + 1) % D;            // slot of step kb + 1
+                if (kb + D < nfull) {                  // refill the free slot with step kb + D
+                    fa.fetch(ra[u], na, tid);
+                    fb.fetch(rb[u], nb, tid);
+                    na += step_a;
+                    nb += step_b;
+                }
+                if (next == nfull && next < nkb) {     // the partial last step: checked fetch, zero filled
+                    const int k0 = kbeg + next * BK;
+                    panel16_fetch_checked<A_KC, BM, THREADS, NVA>(ra[un], g.A, g.lda, i0, g.M, k0, kend, tid);
+                    panel16_fetch_checked<B_KC, BN, THREADS, NVB>(rb[un], g.B, g.ldb, j0, g.N, k0, kend, tid);
+                }
+                compute(cur);
+                if (next < nkb) {
+                    panel16_store<A_KC, BM, THREADS, NVA>(stage_a(cur ^ 1), ra[un], tid);
+                    panel16_store<B_KC, BN, THREADS, NVB>(stage_b(cur ^ 1), rb[un], tid);
+                }
+                __syncthreads();
+            }
+        }
     }
-    for (; kb < nkb; ++kb) {
+    // Steps from nfull on: the one partial step after full ones (already in LDS), or every step of an operand
+    // without 16-byte aligned rows (nfull == 0).
+    for (int kb = nfull; kb < nkb; ++kb) {
         const int cur = kb & 1;
         const bool more = kb + 1 < nkb;
         if (more) {
             const int k0 = kbeg + (kb + 1) * BK;
-            panel16_fetch_checked<A_KC, BM, THREADS, NVA>(ra, g.A, g.lda, i0, g.M, k0, kend, tid);
-            panel16_fetch_checked<B_KC, BN, THREADS, NVB>(rb, g.B, g.ldb, j0, g.N, k0, kend, tid);
+            panel16_fetch_checked<A_KC, BM, THREADS, NVA>(ra[0], g.A, g.lda, i0, g.M, k0, kend, tid);
+            panel16_fetch_checked<B_KC, BN, THREADS, NVB>(rb[0], g.B, g.ldb, j0, g.N, k0, kend, tid);
         }
         compute(cur);
         if (more) {
-            panel16_store<A_KC, BM, THREADS, NVA>(stage_a(cur ^ 1), ra, tid);
-            panel16_store<B_KC, BN, THREADS, NVB>(stage_b(cur ^ 1), rb, tid);
+            panel16_store<A_KC, BM, THREADS, NVA>(stage_a(cur ^ 1), ra[0], tid);
+            panel16_store<B_KC, BN, THREADS, NVB>(stage_b(cur ^ 1), rb[0], tid);
         }
         __syncthreads();
     }

@@ -310,17 +310,17 @@ hipError_t launch_dw1_with_tail(const GemmPlan &p, GemmArgs a, const TailWork &t
 // bf16-operand GEMM dispatch (fp32 accumulation): two tile shapes, same cost model with the measured bf16 rate
 // ---------------------------------------------------------------------------------------------------------
 
-using T16_128 = Tile16<128, 128, 2, 2, 3>;   // 256 threads, 3 workgroups / CU
-using T16_64 = Tile16<64, 64, 2, 2, 8>;      // 256 threads, 8 workgroups / CU
+using T16_128 = Tile16<128, 128, 2, 2, 4, 1>;   // 256 threads, 4 workgroups / CU (LDS 39 KB each)
+using T16_64 = Tile16<64, 64, 2, 2, 8, 1>;      // 256 threads, 8 workgroups / CU
 // Wavefront sub-tile 128 x 64: a third fewer LDS bytes per matrix instruction than 64 x 64 (the 128x128 shape is
 // bound by LDS reads).  Two workgroups per CU, so the epilogue's stores are poorly hidden: long-k products only.
-using T16_256 = Tile16<256, 128, 2, 2, 2>;
+using T16_256 = Tile16<256, 128, 2, 2, 2, 2>;
 
 enum Cfg16Id { CFG16_128 = 0, CFG16_64, CFG16_256, CFG16_COUNT };
 constexpr int CFG16_256_MIN_K = 1024;
 
 constexpr CfgInfo CFG16_INFO[CFG16_COUNT] = {
-    {128, 128, 32, 256, 3, 1.00, "bf16 128x128"},
+    {128, 128, 32, 256, 4, 1.00, "bf16 128x128"},
     {64, 64, 32, 256, 8, 0.70, "bf16 64x64"},
     {256, 128, 32, 256, 2, 1.30, "bf16 256x128"},
 };
