@@ -219,7 +219,7 @@ def main():
             ulsnn.mlp_grad(sW1, sW2, sX, sy, sb1, sb2, out=sout, workspace=sws)
         torch.cuda.synchronize()
         sec = (time.perf_counter() - t1) / 200
-        result["small_net"] = {"workload": "64-32-10 with biases, batch 256 (launch-latency bound: ten launches)",
+        result["small_net"] = {"workload": "64-32-10 with biases, batch 256 (small-network path: two launches; latency bound)",
                                "us_per_call": round(sec * 1e6, 2), "patterns_per_s": round(256 / sec, 1),
                                "gflops": round(ulsnn.mlp_grad_flops(sm.n_in, sm.n_hid, sm.n_out, 256) / sec / 1e9, 2)}
     if args.epoch:

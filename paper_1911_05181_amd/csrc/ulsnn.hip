@@ -12,6 +12,7 @@
 #include "gemm.hpp"
 #include "gemm_bf16.hpp"
 #include "mlp_kernels.hpp"
+#include "small_net.hpp"
 #include "vec_kernels.hpp"
 
 using namespace ulsnn;
@@ -417,6 +418,25 @@ bool desc_ok(const ulsnn_mlp_desc *d)
 
 // Sizes depend on the network and on min(batch, SLAB_ROWS) only, and do not decrease with the batch, so a
 // workspace sized for a batch also serves every smaller one.
+// Small networks at small batches take a two-launch path (small_net.hpp).  Its scratch: one share of every sum
+// per workgroup of SMALL_ROWS patterns.
+inline int small_net_stride(const ulsnn_mlp_desc *d)
+{
+    return (int)round_up((size_t)d->n_in * d->n_hid + (size_t)d->n_hid * d->n_out + d->n_hid + d->n_out + 1, 4);
+}
+inline bool small_net_shape(const ulsnn_mlp_desc *d, long long batch)
+{
+    return d->operand_dtype == 0 && d->n_in <= SMALL_MAX_IN && d->n_hid <= SMALL_MAX_HID &&
+           d->n_out <= SMALL_MAX_OUT && batch >= 1 && batch <= SMALL_MAX_BATCH &&
+           (size_t)small_net_lds_floats(d->n_in, d->n_hid, d->n_out) * sizeof(float) <= 64 * 1024;
+}
+inline size_t small_net_bytes(const ulsnn_mlp_desc *d, long long batch)
+{
+    if (!small_net_shape(d, batch)) return 0;
+    const size_t groups = (size_t)(batch + SMALL_ROWS - 1) / SMALL_ROWS;
+    return round_up(groups * small_net_stride(d) * sizeof(float), 256);
+}
+
 MlpLayout mlp_layout(const ulsnn_mlp_desc *d, int batch)
 {
     MlpLayout L{};
@@ -443,7 +463,7 @@ MlpLayout mlp_layout(const ulsnn_mlp_desc *d, int batch)
         L.off_w1p = off;  off += round_up((size_t)d->n_in * L.ldw1p * 2, 256);
         L.off_w2p = off;  off += round_up((size_t)d->n_hid * L.ldw2p * 2, 256);
     }
-    L.bytes = off;
+    L.bytes = std::max(off, small_net_bytes(d, batch));
     return L;
 }
 
@@ -534,6 +554,29 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, con
         return mlp_grad_impl16(d, (const u16 *)W1v, (const u16 *)W2v, (const u16 *)Xv, task, batch, dW1, dW2, loss,
                                accumulate, ev);
     const float *W1 = (const float *)W1v, *W2 = (const float *)W2v, *X = (const float *)Xv;
+
+    // small network, small batch, softmax form, no stage timing asked for: two launches instead of nine
+    if (!ev && !task.targets && small_net_shape(d, batch)) {
+        const size_t need = mlp_layout(d, batch).bytes;
+        if (!d->workspace || ((uintptr_t)d->workspace & 255) || d->workspace_bytes < need) return ULSNN_ERR_WORKSPACE;
+        SmallNetArgs a{};
+        a.n_in = n_in; a.n_hid = n_hid; a.n_out = n_out; a.batch = batch;
+        a.W1 = W1; a.W2 = W2; a.b1 = d->b1; a.b2 = d->b2; a.X = X; a.labels = task.labels;
+        a.partial = (float *)d->workspace; a.stride = small_net_stride(d); a.backward = task.backward ? 1 : 0;
+        const int groups = (batch + SMALL_ROWS - 1) / SMALL_ROWS;
+        const size_t lds = (size_t)small_net_lds_floats(n_in, n_hid, n_out) * sizeof(float);
+        hipLaunchKernelGGL(small_net_kernel, dim3(groups), dim3(256), lds, s, a);
+        SmallReduceArgs r{};
+        r.partial = a.partial; r.stride = a.stride; r.groups = groups;
+        r.n1 = n_in * n_hid; r.n2 = n_hid * n_out; r.n_hid = n_hid; r.n_out = n_out;
+        r.dW1 = task.backward ? dW1 : nullptr; r.dW2 = task.backward ? dW2 : nullptr;
+        r.db1 = task.backward ? d->db1 : nullptr; r.db2 = task.backward ? d->db2 : nullptr;
+        r.loss = loss; r.beta = accumulate ? 1.0f : 0.0f;
+        const int total = r.n1 + r.n2 + n_hid + n_out + 1;
+        hipLaunchKernelGGL(small_reduce_kernel, dim3(task.backward ? (total + 255) / 256 : 1), dim3(256), 0, s, r);
+        HIP_TRY(hipGetLastError());
+        return ULSNN_OK;
+    }
 
     const MlpLayout L = mlp_layout(d, batch);
     if (!d->workspace || ((uintptr_t)d->workspace & 255) || d->workspace_bytes < L.bytes)

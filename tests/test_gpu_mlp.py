@@ -90,6 +90,11 @@ def test_jocr_network_full_batch():
     ref = _oracle_grad(*p)
     res = _gpu_grad(*p)
     _compare(res, ref, "400-480-3203 B=4096")
+    # how far a plain fp32 evaluation (the float oracle, sums in index order) is from the double one: the GPU's
+    # distance above is of this size, so the 1e-4 bound is a bound on real errors, not on rounding noise
+    f32 = oracle.mlp_grad(*(_np(t) for t in (p[0], p[1], p[4], p[5])), dtype=np.float32)
+    print(f"float oracle vs double oracle: dW1 {_rel(f32.dW1, ref.dW1):.2e} dW2 {_rel(f32.dW2, ref.dW2):.2e}")
+    assert _rel(f32.dW1, ref.dW1) < 1e-5 and _rel(f32.dW2, ref.dW2) < 1e-5
     again = _gpu_grad(*p)
     torch.cuda.synchronize()
     assert torch.equal(res.dW1, again.dW1) and torch.equal(res.dW2, again.dW2) and torch.equal(res.loss, again.loss)
@@ -219,3 +224,32 @@ def test_full_size_epoch_9_million_patterns():
     got = ulsnn.mlp_grad(W1, W2, X[p0:p0 + 4096], y[p0:p0 + 4096])
     torch.cuda.synchronize()
     _compare(got, _oracle_grad(W1.cpu(), W2.cpu(), None, None, Xc, yc), "chunk 17 prefix of the epoch")
+
+
+@pytest.mark.parametrize("n_in,n_hid,n_out,batch,biases", [(64, 32, 10, 256, True), (128, 64, 40, 1000, False),
+                                                          (5, 4, 3, 7, True), (17, 33, 5, 1, True),
+                                                          (100, 64, 64, 4096, False), (64, 32, 10, 4097, True)])
+def test_small_network_path_against_oracle_and_general_path(n_in, n_hid, n_out, batch, biases):
+    """Small nets at small batches run as two launches (one workgroup per 16 patterns, then a sum of the shares).
+    The event-timed entry point always takes the general path: both must agree with the oracle and each other.
+    (The last case is one pattern over the small path's batch limit: general path on both sides.)"""
+    p = _problem(si.MlpShape(n_in, n_hid, n_out, biases), 3, batch, random_biases=True)
+    W1, W2, b1, b2, X, y = p
+    ref = _oracle_grad(*p)
+    small = _gpu_grad(*p)
+    _compare(small, ref, f"small path {n_in}-{n_hid}-{n_out} B={batch}")
+    general, _ = ulsnn.mlp_grad_timed(_dev(W1), _dev(W2), _dev(X), _dev(y), _dev(b1), _dev(b2))
+    _compare(general, ref, f"general path {n_in}-{n_hid}-{n_out} B={batch}")
+    for name in ("dW1", "dW2"):
+        assert _rel(getattr(small, name).cpu().numpy(), getattr(general, name).cpu().numpy().astype(np.float64)) < 1e-5
+    # error-only evaluation, accumulation and ignored labels on the same path
+    only = ulsnn.mlp_loss(_dev(W1), _dev(W2), _dev(X), _dev(y), _dev(b1), _dev(b2))
+    torch.cuda.synchronize()
+    assert abs(only.item() - ref.loss) <= TOL_LOSS * ref.loss
+    twice = _gpu_grad(*p)
+    ulsnn.mlp_grad(_dev(W1), _dev(W2), _dev(X), _dev(y), _dev(b1), _dev(b2), out=twice, accumulate=True)
+    torch.cuda.synchronize()
+    assert _rel(twice.dW2.cpu().numpy(), 2 * ref.dW2) <= TOL_GRAD and abs(twice.loss.item() - 2 * ref.loss) <= 2e-5 * ref.loss
+    y2 = y.clone()
+    y2[::3] = -1
+    _compare(_gpu_grad(W1, W2, b1, b2, X, y2), _oracle_grad(W1, W2, b1, b2, X, y2), "small path, ignored labels")
