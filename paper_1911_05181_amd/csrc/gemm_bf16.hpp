@@ -51,6 +51,8 @@ struct Gemm16Args {
     int tiles_m, tiles_n;
     size_t partial_stride; // EPI_PARTIAL: elements between consecutive partial results
     int aligned;           // 1: A and B rows are 16-byte aligned (fast vector fetch allowed)
+    int c_vec;             // 1: rows of C are 16-byte aligned (pointer and ldc): row-wise vector epilogue
+    int aux_vec;           // 1: rows of aux are 16-byte aligned
 };
 
 // PREFETCH_ = k steps kept in flight in registers.  A bf16 step is eight times shorter on the matrix cores than an
@@ -297,7 +299,29 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
     };
 
     // Full steps 0 .. nfull-1.  On entry to step kb its panels are in LDS stage kb & 1 and slot kb % D is free.
-    for (int base = 0; base < nfull; base += D) {
+    // Steady state first: while every step of a round of D still has a step D ahead to fetch, the round is
+    // branch-free, so the compiler's wait for the slot being stored leaves the newer loads in flight (at a join
+    // of "fetched" and "not fetched" paths it would have to wait for everything, which defeats the pipeline).
+    int base = 0;
+    if constexpr (D > 1) {
+    for (; base + 2 * D <= nfull; base += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int cur = (base + u) & 1;
+            const int un = (u + 1) % D;
+            fa.fetch(ra[u], na, tid);
+            fb.fetch(rb[u], nb, tid);
+            na += step_a;
+            nb += step_b;
+            compute(cur);
+            panel16_store<A_KC, BM, THREADS, NVA>(stage_a(cur ^ 1), ra[un], tid);
+            panel16_store<B_KC, BN, THREADS, NVB>(stage_b(cur ^ 1), rb[un], tid);
+            __syncthreads();
+        }
+    }
+    }
+    // Drain: the last rounds, where fetches run out (with a single slot: every step).
+    for (; base < nfull; base += D) {
 #pragma unroll
         for (int u = 0; u < D; ++u) {
             const int kb = base + u;
@@ -342,13 +366,105 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
         __syncthreads();
     }
 
-    // Epilogue: accumulator register r of a block holds row 8*(r/4) + 4*h + r%4, column lane%32.
+    // Epilogue.  Accumulator register r of a block holds row 8*(r/4) + 4*h + r%4, column lane%32: a lane owns a
+    // COLUMN of the block, so stores straight from the accumulators are one element per lane and instruction
+    // (2 bytes for bf16 results).  With 16-byte aligned rows of C (and of aux) each block instead goes through a
+    // wavefront-private LDS scratch and leaves as rows: every lane handles 8 consecutive columns of one row with
+    // 16-byte loads and stores, an eighth of the memory instructions.
     float *Cf = (float *)g.C;
     u16 *Ch = (u16 *)g.C;
     int ldc = g.ldc;
     if (EPI == EPI_PARTIAL) {
         Cf += (size_t)z * g.partial_stride;
         ldc = g.N;
+    }
+    const bool rows_vec = (EPI == EPI_PARTIAL) ? ((g.N & 3) == 0 && (g.partial_stride & 3) == 0 && g.c_vec) : g.c_vec != 0;
+    if (rows_vec) {
+        constexpr int SLD = 36;                                   // scratch row stride (floats): 16-byte aligned rows
+        static_assert(gemm16_lds_elems<Cfg, A_KC, B_KC>() * 2 >= Cfg::WM * Cfg::WN * 32 * SLD * 4, "scratch fits in the panels' LDS");
+        __syncthreads();                                          // every wavefront is done reading the panels
+        float *scr = reinterpret_cast<float *>(lds) + wave * (32 * SLD);
+        const int srow = lane >> 2, scol = (lane & 3) * 8;        // this lane's row (of 16 per pass) and 8 columns
+#pragma unroll
+        for (int x = 0; x < TM; ++x) {
+#pragma unroll
+            for (int y = 0; y < TN; ++y) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) scr[(8 * (r / 4) + 4 * h + (r % 4)) * SLD + l32] = acc[x][y][r];
+                // LDS operations of one wavefront complete in order; the fences keep the compiler from moving the
+                // reads of other lanes' elements above these writes (and the next block's writes above the reads)
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int pass = 0; pass < 2; ++pass) {
+                    const int row = pass * 16 + srow;
+                    const floatx4 lo = *reinterpret_cast<const floatx4 *>(scr + row * SLD + scol);
+                    const floatx4 hi = *reinterpret_cast<const floatx4 *>(scr + row * SLD + scol + 4);
+                    if (pass == 1) {
+                        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                    }
+                    float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                    const int i = i0 + wrow + x * 32 + row;
+                    const int j = j0 + wcol + y * 32 + scol;
+                    if (i >= g.M || j >= g.N) continue;
+                    const bool whole = j + 7 < g.N;
+                    const size_t at = (size_t)i * ldc + j;
+                    if (EPI == EPI_BIAS_TANH || EPI == EPI_BIAS) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] += (g.bias && j + e < g.N) ? g.bias[j + e] : 0.f;
+                    }
+                    if (EPI == EPI_TANHGRAD) {
+                        const u16 *ap = g.aux + (size_t)i * g.ldaux + j;
+                        u16x8 hv;
+                        if (whole && g.aux_vec) {
+                            hv = load8_aligned(ap);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) hv[e] = j + e < g.N ? ap[e] : (u16)0;
+                        }
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const float t = bf16_to_f32(hv[e]);
+                            v[e] *= (1.0f - t * t);
+                        }
+                    }
+                    if (EPI == EPI_BIAS_TANH) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = tanh_f32(v[e]);
+                    }
+                    if (OUT_BF16) {
+                        u16x8 o;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) o[e] = f32_to_bf16(v[e]);
+                        if (whole) {
+                            *reinterpret_cast<u16x8 *>(Ch + at) = o;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (j + e < g.N) Ch[at + e] = o[e];
+                        }
+                    } else {
+                        if (EPI == EPI_AXPBY) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                v[e] *= g.alpha;
+                                if (g.beta != 0.f && j + e < g.N) v[e] += g.beta * Cf[at + e];
+                            }
+                        }
+                        if (whole) {
+                            *reinterpret_cast<floatx4 *>(Cf + at) = floatx4{v[0], v[1], v[2], v[3]};
+                            *reinterpret_cast<floatx4 *>(Cf + at + 4) = floatx4{v[4], v[5], v[6], v[7]};
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (j + e < g.N) Cf[at + e] = v[e];
+                        }
+                    }
+                }
+            }
+        }
+        return;
     }
 #pragma unroll
     for (int y = 0; y < TN; ++y) {
