@@ -31,7 +31,7 @@ PEAK_FP32_MFMA_TFLOPS = 157.3      # 256 CUs x 256 flop/clk/CU x 2.4 GHz
 # HBM bytes per launch of the dominant kernel (paired backward products, batch 4096): rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB copy (2.000 and 1.000); 275.1 MB read,
 # 56.1 MB written.  Source: profiles/mlp_grad_b4096_hbm_traffic_pmc.md.  Algorithmic: 119.0 MB read, 54.3 MB written.
-PMC_TRAFFIC_BYTES = {"backward_products": 327.5e6}
+PMC_TRAFFIC_BYTES = {"backward_products": 244.2e6}
 METRIC = "fp32 GFLOP/s (% of MFMA FP32 peak); MLP gradient patterns/sec"
 BATCH = 4096
 SEED = 2
