@@ -181,7 +181,9 @@ int ulsnn_mlp_grad_timed(const ulsnn_mlp_desc *desc, const void *W1, const void 
 /*
  * Host-only diagnostic: writes to buf (NUL-terminated, truncated to buf_bytes) one line per matrix product of
  * the gradient (section 4.2) with the tile shape, tile grid, k split and modelled time this build would use
- * for `batch` patterns (for the first internal pass if the batch is processed in several).  Launches nothing.
+ * for `batch` patterns (for the first internal pass if the batch is processed in several).  The first line also
+ * says whether the call would take the two-launch path for small networks instead (small_network_path=1: nets up
+ * to 128-64-64 at up to 4096 patterns, softmax form, fp32).  Launches nothing.
  */
 int ulsnn_mlp_grad_describe_plan(const ulsnn_mlp_desc *desc, int batch, char *buf, size_t buf_bytes);
 

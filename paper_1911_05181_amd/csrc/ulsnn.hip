@@ -1223,8 +1223,8 @@ int ulsnn_mlp_grad_describe_plan(const ulsnn_mlp_desc *desc, int batch, char *bu
     const GemmPlan *g[5] = {&P.g1, &P.g2, &P.g3, &P.g4, &P.g5};
     const char *what[5] = {"hidden_layer", "output_layer", "dW2", "hidden_delta", "dW1"};
     size_t used = 0;
-    int n = snprintf(buf, buf_bytes, "rows_per_pass=%d paired_backward=%d workspace_bytes=%zu\n", L.slab,
-                     (int)P.paired, L.bytes);
+    int n = snprintf(buf, buf_bytes, "rows_per_pass=%d paired_backward=%d workspace_bytes=%zu small_network_path=%d\n",
+                     L.slab, (int)P.paired, L.bytes, (int)small_net_shape(desc, batch));
     if (n > 0) used = std::min((size_t)n, buf_bytes - 1);
     for (int i = 0; i < 5 && used + 1 < buf_bytes; ++i) {
         n = snprintf(buf + used, buf_bytes - used, "%s: tile=%s tiles=%dx%d splits=%d kchunk=%d model_us=%.1f\n",
