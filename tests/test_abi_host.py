@@ -111,7 +111,7 @@ def test_sgemm_planned_argument_errors_and_plan_description():
     p = C.c_void_p(0x1000)
     f = lambda tile, sp, ta, tb, m, n, k, ws=None, wsb=0: L.ulsnn_sgemm_planned(
         tile, sp, ta, tb, m, n, k, 1.0, p, max(k, m, 1), p, max(n, k, 1), 0.0, p, max(n, 1), ws, wsb, None)
-    assert f(7, 1, b"N", b"N", 8, 8, 8) == E_DIM           # no such tile shape
+    assert f(len(ulsnn.TILE_SHAPES), 1, b"N", b"N", 8, 8, 8) == E_DIM           # no such tile shape
     assert f(-1, 1, b"N", b"N", 8, 8, 8) == E_DIM
     assert f(0, 0, b"N", b"N", 8, 8, 8) == E_DIM           # k_splits < 1
     assert f(0, 1, b"X", b"N", 8, 8, 8) == E_TRANS
