@@ -253,3 +253,38 @@ def test_small_network_path_against_oracle_and_general_path(n_in, n_hid, n_out, 
     y2 = y.clone()
     y2[::3] = -1
     _compare(_gpu_grad(W1, W2, b1, b2, X, y2), _oracle_grad(W1, W2, b1, b2, X, y2), "small path, ignored labels")
+
+
+@pytest.mark.parametrize("n_in,n_hid,n_out,batch", [(64, 32, 10, 256), (100, 130, 259, 300), (400, 480, 3203, 1024)])
+def test_gradient_call_can_be_captured_in_a_hip_graph(n_in, n_hid, n_out, batch):
+    """The entry point only enqueues kernels on the caller's stream (no allocation, no memset, no synchronisation),
+    so a caller may capture it in a HIP graph.  Every replay, with eager calls and synchronisations in between,
+    must reproduce the eager result bit for bit, and that result must match the oracle."""
+    p = _problem(si.MlpShape(n_in, n_hid, n_out, True), 11, batch, random_biases=True)
+    W1, W2, b1, b2, X, y = (_dev(t) for t in p)
+    ws = torch.empty(ulsnn.mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch), dtype=torch.uint8, device=DEV)
+
+    def fresh():
+        return ulsnn.MlpGradResult(torch.empty_like(W1), torch.empty_like(W2), torch.empty(1, device=DEV),
+                                   torch.empty_like(b1), torch.empty_like(b2))
+
+    eager, replayed = fresh(), fresh()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ulsnn.mlp_grad(W1, W2, X, y, b1, b2, out=replayed, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ulsnn.mlp_grad(W1, W2, X, y, b1, b2, out=replayed, workspace=ws)
+    for _ in range(3):
+        for t in (replayed.dW1, replayed.dW2, replayed.db1, replayed.db2, replayed.loss):
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        ulsnn.mlp_grad(W1, W2, X, y, b1, b2, out=eager, workspace=ws)
+        torch.cuda.synchronize()
+        for name in ("dW1", "dW2", "db1", "db2", "loss"):
+            assert torch.equal(getattr(replayed, name), getattr(eager, name)), name
+    _compare(replayed, _oracle_grad(*p), f"graph replay {n_in}-{n_hid}-{n_out} B={batch}")
