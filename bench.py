@@ -29,8 +29,8 @@ if ROOT not in sys.path:
 
 PEAK_FP32_MFMA_TFLOPS = 157.3      # 256 CUs x 256 flop/clk/CU x 2.4 GHz
 # HBM bytes per launch of the dominant kernel (paired backward products, batch 4096): rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB copy (2.000 and 1.000); 275.1 MB read,
-# 56.1 MB written.  Source: profiles/mlp_grad_b4096_hbm_traffic_pmc.md.  Algorithmic: 119.0 MB read, 54.3 MB written.
+# WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB copy (2.000 and 1.000); 188.7 MB read,
+# 55.5 MB written.  Source: profiles/mlp_grad_b4096_hbm_traffic_pmc.md.  Algorithmic: 119.0 MB read, 54.3 MB written.
 PMC_TRAFFIC_BYTES = {"backward_products": 244.2e6}
 METRIC = "fp32 GFLOP/s (% of MFMA FP32 peak); MLP gradient patterns/sec"
 BATCH = 4096
@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--no-bf16", action="store_true", help="skip the bf16-operand workload (batch 65536)")
     ap.add_argument("--no-large-batch", action="store_true", help="skip the fp32 batch-262144 chunk measurement")
     ap.add_argument("--no-small-net", action="store_true", help="skip the 64-32-10 latency measurement")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip the squared-error, error-only and optimiser-step measurements (batch 4096)")
     ap.add_argument("--epoch", action="store_true",
                     help="also time the whole 9,000,000-pattern epoch (14.4 GB of patterns generated on the GPU)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -105,6 +107,74 @@ def cpu_baseline(si, shape, W1, W2, X, y):
     return {"value": round(flops / dt / 1e9, 3), "unit": "GFLOP/s", "cores": oracle.threads(), "kind": "oracle",
             "sample": f"the whole workload once: {X.shape[0]} patterns, float-arithmetic oracle, {dt:.2f} s",
             "patterns_per_s": round(X.shape[0] / dt, 1), "loss": g.loss}
+
+
+def bench_variants(ulsnn, si, torch, shape, W1, W2, X, y, ws):
+    """The other entry points on the same network and batch: squared-error gradient (section 4.2), error-only
+    evaluation, one conjugate-gradient iteration (gradient + Polak-Ribiere direction + line search), and the
+    vector primitives over the 1,729,440 weights."""
+    dev, b = X.device, X.shape[0]
+    n_i, n_h, n_o = shape.n_in, shape.n_hid, shape.n_out
+    out = ulsnn.MlpGradResult(torch.empty_like(W1), torch.empty_like(W2), torch.empty(1, device=dev))
+
+    def per_call(f, reps):
+        for _ in range(3):
+            f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            f()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    res = {}
+    T = si.mlp_targets(shape, SEED, 0, b, device=dev)
+    sec = per_call(lambda: ulsnn.mlp_grad_mse(W1, W2, X, T, out=out, workspace=ws), 30)
+    fl = ulsnn.mlp_grad_flops(n_i, n_h, n_o, b)
+    res["mse_grad"] = {"ms": round(sec * 1e3, 4), "gflops": round(fl / sec / 1e9, 1),
+                       "frac_of_fp32_mfma_peak": round(fl / sec / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4)}
+    del T
+    loss = torch.empty(1, device=dev)
+    sec = per_call(lambda: ulsnn.mlp_loss(W1, W2, X, y, loss=loss, workspace=ws), 30)
+    fl = ulsnn.mlp_loss_flops(n_i, n_h, n_o, b)
+    res["loss_only"] = {"ms": round(sec * 1e3, 4), "gflops": round(fl / sec / 1e9, 1),
+                        "frac_of_fp32_mfma_peak": round(fl / sec / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4)}
+
+    # one conjugate-gradient iteration from the initial weights, repeated from the same start
+    n1 = W1.numel()
+    grad = torch.empty(n1 + W2.numel(), device=dev)
+    d = torch.empty_like(grad)
+    gout = ulsnn.MlpGradResult(grad[:n1].view_as(W1), grad[n1:].view_as(W2), torch.empty(1, device=dev))
+    lws = torch.empty(ulsnn.mlp_line_search_workspace_bytes(n_i, n_h, n_o, b), dtype=torch.uint8, device=dev)
+    bracket, last = 512, None
+    times = []
+    for rep in range(4):
+        V1, V2 = W1.clone(), W2.clone()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ulsnn.mlp_grad(V1, V2, X, y, out=gout, workspace=ws)
+        ulsnn.cg_direction(grad, None, d)
+        last = ulsnn.mlp_line_search(V1, V2, d[:n1].view_as(W1), d[n1:].view_as(W2), X, y, bracket, 1e-5, 30,
+                                     workspace=lws)
+        torch.cuda.synchronize()
+        if rep:
+            times.append(time.perf_counter() - t0)
+    sec = min(times)
+    fl = (ulsnn.mlp_grad_flops(n_i, n_h, n_o, b) + last.error_evaluations * ulsnn.mlp_loss_flops(n_i, n_h, n_o, b)
+          + last.gradient_evaluations * ulsnn.mlp_grad_flops(n_i, n_h, n_o, bracket))
+    res["cg_iteration"] = {"ms": round(sec * 1e3, 3), "gflops": round(fl / sec / 1e9, 1),
+                           "error_evaluations": last.error_evaluations,
+                           "gradient_evaluations_on_subset": last.gradient_evaluations, "bracket_batch": bracket,
+                           "alpha": last.alpha, "loss_before": last.loss0, "loss_after": last.loss,
+                           "note": "host reads two scalars per evaluation: latency of the evaluations dominates"}
+    # vector primitives: HBM/L2-resident 6.9 MB vectors, launch-latency bound
+    dot_out = torch.empty(1, device=dev)
+    vws = torch.empty(ulsnn.VEC_WORKSPACE_BYTES, dtype=torch.uint8, device=dev)
+    sec = per_call(lambda: ulsnn.dot(grad, d, out=dot_out, workspace=vws), 200)
+    res["dot"] = {"us": round(sec * 1e6, 2), "GB_per_s": round(2 * grad.numel() * 4 / sec / 1e9, 1)}
+    sec = per_call(lambda: ulsnn.axpy(1e-9, grad, d), 200)
+    res["axpy"] = {"us": round(sec * 1e6, 2), "GB_per_s": round(3 * grad.numel() * 4 / sec / 1e9, 1)}
+    return res
 
 
 def main():
@@ -222,6 +292,8 @@ def main():
         result["small_net"] = {"workload": "64-32-10 with biases, batch 256 (small-network path: two launches; latency bound)",
                                "us_per_call": round(sec * 1e6, 2), "patterns_per_s": round(256 / sec, 1),
                                "gflops": round(ulsnn.mlp_grad_flops(sm.n_in, sm.n_hid, sm.n_out, 256) / sec / 1e9, 2)}
+    if not args.no_variants:
+        result["variants"] = bench_variants(ulsnn, si, torch, shape, W1, W2, X, y, ws)
     if args.epoch:
         # the epoch workload (BASELINE configs[3]): 9,000,000 patterns resident in HBM, chunks of 262144 summed
         n_ep, chunk = 9_000_000, 262144
