@@ -253,9 +253,11 @@ int ulsnn_mlp_line_search(const ulsnn_mlp_desc *desc, float *W1, float *W2, cons
 #define ULSNN_TILE_128x64 3
 #define ULSNN_TILE_64x128 4
 #define ULSNN_TILE_64x64 5
-#define ULSNN_TILE_64x64_K64 6 /* k step 64 instead of 16: for launches too small to fill the chip */
+#define ULSNN_TILE_64x64_K64 6 /* k step 64, 8 wavefronts: two groups of four each take half of every step; for
+                                  launches too small to fill the chip */
 #define ULSNN_TILE_160x128 7   /* 5 accumulator blocks per wavefront: no padding when a dimension is 480 */
-#define ULSNN_TILE_COUNT 8
+#define ULSNN_TILE_64x64_K32 8 /* k step 32, 8 wavefronts in two groups as above */
+#define ULSNN_TILE_COUNT 9
 int ulsnn_sgemm_planned(int tile_shape, int k_splits, char transa, char transb, int m, int n, int k, float alpha,
                         const float *A, int lda, const float *B, int ldb, float beta, float *C, int ldc,
                         void *workspace, size_t workspace_bytes, void *hip_stream);

@@ -225,7 +225,7 @@ def mlp_line_search(W1, W2, d1, d2, X, labels, bracket_batch: int, alpha0: float
     return res
 
 
-TILE_SHAPES = ("256x128", "128x128w8", "128x128", "128x64", "64x128", "64x64", "64x64k64", "160x128")   # index = ULSNN_TILE_*
+TILE_SHAPES = ("256x128", "128x128w8", "128x128", "128x64", "64x128", "64x64", "64x64k64", "160x128", "64x64k32")   # index = ULSNN_TILE_*
 
 
 def sgemm_planned(tile_shape: int, k_splits: int, transa: str, transb: str, m: int, n: int, k: int, alpha: float,

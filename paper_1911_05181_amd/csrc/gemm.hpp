@@ -60,13 +60,17 @@ struct GemmArgs {
 #endif
 
 // WAVES_PER_SIMD_ is the occupancy the register allocation must allow (wavefronts per SIMD).
-template <int BM_, int BN_, int BK_, int WM_, int WN_, int WAVES_PER_SIMD_ = 1>
+// KW_ > 1: KW_ groups of WM x WN wavefronts share the tile; each group takes 1/KW_ of every k step and the
+// groups' accumulators are added through LDS before the epilogue (in group order, so the sum is reproducible).
+// It gives a launch with few workgroups per compute unit more wavefronts per SIMD to hide latency with.
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int WAVES_PER_SIMD_ = 1, int KW_ = 1>
 struct TileCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, WAVES_PER_SIMD = WAVES_PER_SIMD_;
-    static constexpr int THREADS = WM * WN * 64;
+    static constexpr int KW = KW_;
+    static constexpr int THREADS = WM * WN * KW * 64;
     static constexpr int WTM = BM / WM, WTN = BN / WN;   // wavefront sub-tile
     static constexpr int TM = WTM / 32, TN = WTN / 32;   // 32x32 accumulator blocks per wavefront
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % 8 == 0, "tile shape");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % 8 == 0 && (BK / 8) % KW == 0, "tile shape");
 };
 
 // LDS footprint (floats) of one stage of one operand panel with R rows/columns of C
@@ -374,7 +378,9 @@ __device__ __forceinline__ void gemm_segment(const GemmArgs &g, const int tile_m
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
-    const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
+    const int kw = wave / (Cfg::WM * Cfg::WN);               // which share of every k step (0 when KW == 1)
+    const int wave_mn = wave % (Cfg::WM * Cfg::WN);
+    const int wm = wave_mn / Cfg::WN, wn = wave_mn % Cfg::WN;
     const int wrow = wm * Cfg::WTM, wcol = wn * Cfg::WTN;
 
     const int i0 = tile_m * BM, j0 = tile_n * BN;
@@ -441,11 +447,13 @@ __device__ __forceinline__ void gemm_segment(const GemmArgs &g, const int tile_m
     // latency of these LDS reads is covered by the products of the other workgroups' wavefronts.
     auto compute = [&](int cur) {
         const float *la = stage_a(cur), *lb = stage_b(cur);
-        Fragments<Cfg> f[S];
+        constexpr int SW = S / Cfg::KW;   // groups of four products per step for this wavefront
+        Fragments<Cfg> f[SW];
 #pragma unroll
-        for (int sg = 0; sg < S; ++sg) read_fragments<Cfg, A_KC, B_KC>(f[sg], la, lb, sg, wrow, wcol, l32, h);
+        for (int sg = 0; sg < SW; ++sg)
+            read_fragments<Cfg, A_KC, B_KC>(f[sg], la, lb, kw * SW + sg, wrow, wcol, l32, h);
 #pragma unroll
-        for (int sg = 0; sg < S; ++sg) multiply<Cfg, 0, 4>(acc, f[sg]);
+        for (int sg = 0; sg < SW; ++sg) multiply<Cfg, 0, 4>(acc, f[sg]);
     };
 
     // full steps whose successor is also a full step: unchecked fetch
@@ -481,6 +489,34 @@ __device__ __forceinline__ void gemm_segment(const GemmArgs &g, const int tile_m
     }
 
     ULSNN_STAMP(2);
+    if (Cfg::KW > 1) {
+        // The k loop ended with a barrier, so the panels are dead: groups 1.. park their accumulators in LDS
+        // (one 64-lane row per register: conflict free), group 0 adds them in group order and goes on alone.
+        constexpr int PER_WAVE = TM * TN * 16 * 64;
+        static_assert((Cfg::KW - 1) * Cfg::WM * Cfg::WN * PER_WAVE <= gemm_lds_floats<Cfg, A_KC, B_KC>(),
+                      "LDS too small for the accumulator exchange");
+        if (kw > 0) {
+            float *dst = lds + ((kw - 1) * Cfg::WM * Cfg::WN + wave_mn) * PER_WAVE + lane;
+#pragma unroll
+            for (int x = 0; x < TM; ++x)
+#pragma unroll
+                for (int y = 0; y < TN; ++y)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) dst[((x * TN + y) * 16 + r) * 64] = acc[x][y][r];
+        }
+        __syncthreads();
+        if (kw > 0) return;
+#pragma unroll
+        for (int g2 = 1; g2 < Cfg::KW; ++g2) {
+            const float *src = lds + ((g2 - 1) * Cfg::WM * Cfg::WN + wave_mn) * PER_WAVE + lane;
+#pragma unroll
+            for (int x = 0; x < TM; ++x)
+#pragma unroll
+                for (int y = 0; y < TN; ++y)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[x][y][r] += src[((x * TN + y) * 16 + r) * 64];
+        }
+    }
     // Epilogue.  Accumulator register r of a 32x32 block holds row 8*(r/4) + 4*h + r%4, column lane%32.
 #pragma unroll
     for (int y = 0; y < TN; ++y) {

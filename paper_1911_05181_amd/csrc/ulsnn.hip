@@ -41,14 +41,19 @@ using Cfg128 = TileCfg<128, 128, 16, 2, 2, 4>;       // 256 threads, 4 workgroup
 using Cfg128x64 = TileCfg<128, 64, 16, 2, 2, 5>;     // 256 threads, 5 workgroups / CU
 using Cfg64x128 = TileCfg<64, 128, 16, 2, 2, 5>;     // 256 threads, 5 workgroups / CU
 using Cfg64 = TileCfg<64, 64, 16, 2, 2, 8>;          // 256 threads, 8 workgroups / CU: small problems
-// The same tile with a k step of 64: a launch that cannot fill the chip (one or two workgroups per CU) is bound
-// by the latency of its chain of k steps, not by the matrix cores; four times fewer, larger steps shorten it.
-using Cfg64k64 = TileCfg<64, 64, 64, 2, 2, 2>;
+// The same tile with a k step of 64 and eight wavefronts, two groups of four that each take half of every step:
+// a launch that cannot fill the chip (one or two workgroups per CU) is bound by the latency of its chain of k
+// steps, not by the matrix cores; four times fewer, larger steps shorten it, and the second group of wavefronts
+// gives every SIMD something to run while the first waits (1024^3: 34.5 us with the plain 64x64 tile, 29.0 with
+// the k step of 64, 26.9 with the two groups).
+using Cfg64k64 = TileCfg<64, 64, 64, 2, 2, 4, 2>;
+// k step 32, two groups of wavefronts, 4 workgroups / CU: for launches of at most four 64x64 workgroups per CU.
+using Cfg64k32 = TileCfg<64, 64, 32, 2, 2, 4, 2>;
 // 160 rows = 5 accumulator blocks per wavefront (sub-tile 160 x 32): three tiles cover a dimension of 480 without
 // padding, where 128-row tiles compute 512.  Measured on dW2 = H^T dO at 32768 patterns: 946 -> 865 us.
 using Cfg160x128 = TileCfg<160, 128, 16, 1, 4, 3>;   // 256 threads, 3 workgroups / CU
 
-enum CfgId { CFG_256x128 = 0, CFG_128W8, CFG_128, CFG_128x64, CFG_64x128, CFG_64, CFG_64K64, CFG_160x128, CFG_COUNT };
+enum CfgId { CFG_256x128 = 0, CFG_128W8, CFG_128, CFG_128x64, CFG_64x128, CFG_64, CFG_64K64, CFG_160x128, CFG_64K32, CFG_COUNT };
 
 struct CfgInfo {
     int bm, bn, bk, threads, occ;   // occ = resident workgroups per compute unit
@@ -60,8 +65,9 @@ constexpr CfgInfo CFG_INFO[CFG_COUNT] = {
     {256, 128, 16, 512, 2, 1.00, "256x128"}, {128, 128, 16, 512, 3, 0.98, "128x128w8"},
     {128, 128, 16, 256, 4, 0.97, "128x128"}, {128, 64, 16, 256, 5, 0.93, "128x64"},
     {64, 128, 16, 256, 5, 0.93, "64x128"},   {64, 64, 16, 256, 8, 0.86, "64x64"},
-    {64, 64, 64, 256, 2, 0.86, "64x64k64"},
+    {64, 64, 64, 512, 2, 0.86, "64x64k64"},
     {160, 128, 16, 256, 3, 1.06, "160x128"},
+    {64, 64, 32, 512, 4, 0.86, "64x64k32"},
 };
 
 struct GemmPlan {
@@ -116,7 +122,7 @@ GemmPlan plan_gemm(int m, int n, int k, bool a_kc, bool b_kc, int split_limit, u
     GemmPlan best{};
     best.est_us = 1e30;
     for (int ci = 0; ci < CFG_COUNT; ++ci) {
-        if (!(cfg_mask >> ci & 1) || ci == CFG_64K64) continue;
+        if (!(cfg_mask >> ci & 1) || ci == CFG_64K64 || ci == CFG_64K32) continue;
         const CfgInfo &c = CFG_INFO[ci];
         // the 160-row shape exists to avoid padding: only where it computes fewer rows than 128-row tiles would
         if (ci == CFG_160x128 && round_up((size_t)m, 160) >= round_up((size_t)m, 128)) continue;
@@ -135,12 +141,22 @@ GemmPlan plan_gemm(int m, int n, int k, bool a_kc, bool b_kc, int split_limit, u
             }
         }
     }
-    // A launch with at most one 64x64 workgroup per compute unit is bound by the latency of its chain of k steps:
-    // take the same tile with four times fewer, larger steps (measured: 1024^3 33 -> 28 us, 512^3 17.7 -> 15.2 us).
-    if (best.cfg == CFG_64 && best.splits == 1 && (cfg_mask >> CFG_64K64 & 1) &&
-        (long)best.tiles_m * best.tiles_n <= NUM_CU && k >= 4 * CFG_INFO[CFG_64K64].bk) {
-        best.cfg = CFG_64K64;
-        best.kchunk = (int)round_up((size_t)k, CFG_INFO[CFG_64K64].bk);
+    // Unsplit 64x64 launches that cannot fill the chip take the eight-wavefront variants of the tile.  Up to four
+    // workgroups per compute unit: k step 32 (2048^3 161 -> 155 us; with more workgroups than that the plain tile's
+    // eight small workgroups per CU do better: output layer at 4096 patterns 120 against 124.5 us).  At most one
+    // workgroup per compute unit: k step 64; the launch is bound by the latency of its chain of k steps
+    // (1024^3 34.5 -> 26.9 us, 512^3 17.8 -> 14.4 us).
+    if (best.cfg == CFG_64 && best.splits == 1) {
+        const long tiles = (long)best.tiles_m * best.tiles_n;
+        CfgId alt = CFG_64;
+        if ((cfg_mask >> CFG_64K32 & 1) && tiles <= 4 * NUM_CU && k >= 4 * CFG_INFO[CFG_64K32].bk &&
+            k % CFG_INFO[CFG_64K32].bk == 0)   // (a partial last step would eat the gain: hidden layer, k = 400)
+            alt = CFG_64K32;
+        if ((cfg_mask >> CFG_64K64 & 1) && tiles <= NUM_CU && k >= 4 * CFG_INFO[CFG_64K64].bk) alt = CFG_64K64;
+        if (alt != CFG_64) {
+            best.cfg = alt;
+            best.kchunk = (int)round_up((size_t)k, CFG_INFO[alt].bk);
+        }
     }
     return best;
 }
@@ -161,6 +177,7 @@ hipError_t with_cfg(CfgId id, F &&f)
         case CFG_64x128: return f(Cfg64x128{});
         case CFG_64K64: return f(Cfg64k64{});
         case CFG_160x128: return f(Cfg160x128{});
+        case CFG_64K32: return f(Cfg64k32{});
         default: return f(Cfg64{});
     }
 }

@@ -122,7 +122,7 @@ def test_sgemm_planned_argument_errors_and_plan_description():
     assert L.ulsnn_sgemm_planned(0, 1, b"N", b"N", 8, 8, 8, 1.0, p, 4, p, 8, 0.0, p, 8, None, 0, None) == E_LD
     line = ulsnn.sgemm_describe_plan("N", "T", 8192, 8192, 8192)
     assert line.startswith("tile=256x128 ") and "splits=1" in line
-    assert ulsnn.sgemm_describe_plan("N", "N", 64, 64, 64).startswith("tile=64x64 ")
+    assert ulsnn.sgemm_describe_plan("N", "N", 64, 64, 64).startswith("tile=64x64")
     assert ulsnn.sgemm_describe_plan("N", "N", 1024, 1024, 1024).startswith("tile=64x64k64 ")   # under-filled launch
     buf = C.create_string_buffer(8)
     assert L.ulsnn_sgemm_describe_plan(b"N", b"N", 0, 8, 8, buf, 8) == E_DIM
