@@ -515,6 +515,12 @@ SlabPlans plan_slab(const MlpLayout &L, int n_in, int n_hid, int n_out, int rows
     s.g3 = plan_gemm(n_hid, n_out, rows, false, false, slices(L.floats_pa, n_hid, n_out), CFGS_256_THREADS);
     s.g4 = plan_gemm(rows, n_hid, n_out, true, true, slices(L.floats_pb, rows, n_hid), CFGS_256_THREADS);
     s.g5 = plan_gemm(n_in, n_hid, rows, false, false, slices(L.floats_pa, n_in, n_hid), CFGS_256_THREADS);
+    // the 256-thread restriction serves the paired launch; an unsplit hidden-delta product runs alone and may take
+    // any shape (32768 patterns: 256x128 instead of 128x128, 20 us of 870)
+    if (s.g4.splits == 1) {
+        const GemmPlan any = plan_gemm(rows, n_hid, n_out, true, true, 1, ALL_CFGS);
+        if (any.est_us < s.g4.est_us) s.g4 = any;
+    }
     s.paired = s.g3.splits > 1 && s.g4.splits > 1 && (CFGS_PAIRABLE >> s.g3.cfg & 1) && (CFGS_PAIRABLE >> s.g4.cfg & 1);
     return s;
 }
