@@ -170,7 +170,7 @@ int ulsnn_mlp_grad_epoch(const ulsnn_mlp_desc *desc, const void *W1, const void 
  *   3 backward products: hidden delta dA1 = dO W2^T and dW2 = H^T dO (one paired launch when both are k-split)
  *   4 their split-k reductions    5 dW1 = X^T dA1 product   6 its split-k reduction      7 bias gradients
  * (section 4.2 names the products; stages 4 and 6 are empty without a k split, 7 without biases).  Only batches that fit one
- * internal pass are accepted (1 <= batch <= 32768), otherwise ULSNN_ERR_UNSUPPORTED.  Creates and destroys
+ * internal pass are accepted (1 <= batch <= 65536), otherwise ULSNN_ERR_UNSUPPORTED.  Creates and destroys
  * HIP events; allocates no device memory.
  */
 #define ULSNN_MLP_STAGES 8

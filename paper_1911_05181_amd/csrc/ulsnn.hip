@@ -21,7 +21,7 @@ namespace {
 
 constexpr int NUM_CU = 256;          // MI355X: 8 XCDs x 32 compute units
 #ifndef ULSNN_SLAB_ROWS
-#define ULSNN_SLAB_ROWS 32768
+#define ULSNN_SLAB_ROWS 65536
 #endif
 constexpr int SLAB_ROWS = ULSNN_SLAB_ROWS;   // patterns processed per internal pass of the MLP gradient
 

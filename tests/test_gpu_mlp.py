@@ -161,7 +161,7 @@ def test_timed_variant_matches_and_reports_stages():
     assert list(ms) == list(ulsnn.MLP_STAGES) and all(v >= 0 for v in ms.values())
     assert ms["output_layer"] > 0 and ms["backward_products"] > 0
     with pytest.raises(ulsnn.UlsnnError) as e:                       # more than one internal pass: refused
-        big = _problem(si.MLP_SMALL, 0, 40_000)
+        big = _problem(si.MLP_SMALL, 0, 70_000)
         ulsnn.mlp_grad_timed(_dev(big[0]), _dev(big[1]), _dev(big[4]), _dev(big[5]))
     assert e.value.status == 6
 

@@ -114,7 +114,7 @@ def test_epoch_and_accumulate():
 
 
 def test_full_size_batch_65536_is_the_sum_of_its_parts():
-    """The bf16 workload at full size (two internal passes of 32768 patterns): the oracle cannot run 65536
+    """The bf16 workload at full size (one internal pass of 65536 patterns): the oracle cannot run 65536
     patterns in seconds, so the whole is checked against the double-precision sum of sixteen 4096-pattern
     gradients from the same path (one of which is checked element by element against the oracle above)."""
     shape, n = si.MLP_JOCR, 65536
@@ -135,6 +135,12 @@ def test_full_size_batch_65536_is_the_sum_of_its_parts():
     e2 = ((whole.dW2.double() - s2).norm() / s2.norm()).item()
     print(f"bf16 B=65536 vs sum of 16 parts: dW1 {e1:.2e} dW2 {e2:.2e}")
     assert e1 < 1e-4 and e2 < 1e-4 and abs(whole.loss.item() - sl) < 1e-4 * sl
+
+
+def test_batch_larger_than_one_internal_pass():
+    """70,000 patterns = two internal passes (small net so the oracle stays quick)."""
+    p = _problem(si.MLP_SMALL, 0, 70_000, random_biases=True)
+    _compare(_gpu(*p), _oracle(*p), "64-32-10 B=70000")
 
 
 def test_mixed_dtypes_are_refused():
