@@ -77,6 +77,9 @@ def test_small_net_with_biases():
     (400, 480, 3203, 257, False),    # the paper's network, a batch with a ragged tail
     (64, 32, 4500, 37, True),        # rows too long for the register softmax
     (33, 7, 2, 1000, False),
+    (1, 1, 1, 3, True),              # degenerate: one class, so every delta and the loss are zero
+    (3, 1, 2, 5, False),             # a single hidden unit
+    (2, 5, 1, 4, True),
 ])
 def test_ragged_shapes(n_in, n_hid, n_out, batch, biases):
     p = _problem(si.MlpShape(n_in, n_hid, n_out, biases), 5, batch, random_biases=True)
