@@ -238,7 +238,15 @@ __global__ __launch_bounds__(1024) void loss_reduce_kernel(const float *__restri
 {
     __shared__ double red[16];
     double s = 0.0;
-    for (long long r = threadIdx.x; r < n; r += 1024) s += (double)row_loss[r];
+    long long r = threadIdx.x;
+    for (; r + 7 * 1024 < n; r += 8 * 1024) {   // eight loads in flight; the additions keep the order of r
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = row_loss[r + u * 1024];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += (double)v[u];
+    }
+    for (; r < n; r += 1024) s += (double)row_loss[r];
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
