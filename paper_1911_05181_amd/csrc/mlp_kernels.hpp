@@ -168,7 +168,13 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
     const size_t total = (size_t)M * N;
     for (size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (size_t)gridDim.x * 256) {
         float s = 0.f;
-        for (int zz = 0; zz < splits; ++zz) s += partial[(size_t)zz * stride + idx];   // fixed order
+        int zz = 0;
+        for (; zz + 3 < splits; zz += 4) {   // four loads in flight; the additions keep the split order
+            const float *q = partial + (size_t)zz * stride + idx;
+            const float p0 = q[0], p1 = q[stride], p2 = q[2 * stride], p3 = q[3 * stride];
+            s = (((s + p0) + p1) + p2) + p3;
+        }
+        for (; zz < splits; ++zz) s += partial[(size_t)zz * stride + idx];
         const int i = (int)(idx / N), j = (int)(idx % N);
         if (MUL_TANHGRAD) {
             const float hv = BF16 ? bf16_to_f32(((const u16 *)aux_v)[(size_t)i * ldaux + j]) : aux[(size_t)i * ldaux + j];

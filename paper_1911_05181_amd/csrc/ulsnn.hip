@@ -301,7 +301,13 @@ __global__ __launch_bounds__(256, Cfg::WAVES_PER_SIMD) void dw1_with_tail_kernel
         const size_t total = (size_t)t.M * t.N;
         for (size_t idx = (size_t)(id - n_gemm) * 256 + threadIdx.x; idx < total; idx += (size_t)t.reduce_blocks * 256) {
             float sum = 0.f;
-            for (int z = 0; z < t.splits; ++z) sum += t.partial[(size_t)z * t.stride + idx];   // fixed order
+            int z = 0;
+            for (; z + 3 < t.splits; z += 4) {   // four loads in flight; the additions keep the split order
+                const float *q = t.partial + (size_t)z * t.stride + idx;
+                const float p0 = q[0], p1 = q[t.stride], p2 = q[2 * t.stride], p3 = q[3 * t.stride];
+                sum = (((sum + p0) + p1) + p2) + p3;
+            }
+            for (; z < t.splits; ++z) sum += t.partial[(size_t)z * t.stride + idx];
             float *dst = t.out + (idx / t.N) * (size_t)t.ldc + (idx % t.N);
             *dst = t.beta != 0.f ? sum + t.beta * *dst : sum;
         }
