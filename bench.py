@@ -30,9 +30,9 @@ if ROOT not in sys.path:
 
 PEAK_FP32_MFMA_TFLOPS = 157.3      # 256 CUs x 256 flop/clk/CU x 2.4 GHz
 # HBM bytes per launch of the dominant kernel (paired backward products, batch 4096): rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB copy (2.000 and 1.000); 190.0 MB read,
+# WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB copy (2.000 and 1.000); 189.5 MB read,
 # 55.4 MB written.  Source: profiles/mlp_grad_b4096_hbm_traffic_pmc.md.  Algorithmic: 119.0 MB read, 54.3 MB written.
-PMC_TRAFFIC_BYTES = {"backward_products": 245.4e6}
+PMC_TRAFFIC_BYTES = {"backward_products": 244.9e6}
 METRIC = "fp32 GFLOP/s (% of MFMA FP32 peak); MLP gradient patterns/sec"
 BATCH = 4096
 SEED = 2
