@@ -61,6 +61,15 @@ def parse():
     return ap.parse_args()
 
 
+def settle(torch, f, seconds):
+    """Run f() untimed for `seconds`: a GPU that has idled (host-side work between two measurements) or a fresh
+    process runs its first tens of milliseconds under load several per cent slower."""
+    t = time.perf_counter()
+    while time.perf_counter() - t < seconds:
+        f()
+        torch.cuda.synchronize()
+
+
 def bench_sgemm(ulsnn, si, torch, sizes):
     """alpha = 1, beta = 0.5, entries uniform[-1,1], seed 1; NN, NT, TN.  `ms` = one call's share of a run of
     back-to-back calls bracketed by two events (throughput; what `gflops` is computed from); `ms_single` = median
@@ -73,9 +82,7 @@ def bench_sgemm(ulsnn, si, torch, sizes):
         for ta, tb in (("N", "N"), ("N", "T"), ("T", "N")):
             Cm = C0.clone()
             reps = 30 if size <= 1024 else (10 if size <= 4096 else 5)
-            for _ in range(3):
-                ulsnn.sgemm(ta, tb, m, n, k, 1.0, A, k, B, n, 0.5, Cm, n)
-            torch.cuda.synchronize()
+            settle(torch, lambda: ulsnn.sgemm(ta, tb, m, n, k, 1.0, A, k, B, n, 0.5, Cm, n), 0.03)
             times = []
             for _ in range(reps):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -122,9 +129,7 @@ def bench_variants(ulsnn, si, torch, shape, W1, W2, X, y, ws):
     out = ulsnn.MlpGradResult(torch.empty_like(W1), torch.empty_like(W2), torch.empty(1, device=dev))
 
     def per_call(f, reps):
-        for _ in range(3):
-            f()
-        torch.cuda.synchronize()
+        settle(torch, f, 0.05)
         t0 = time.perf_counter()
         for _ in range(reps):
             f()
@@ -265,9 +270,7 @@ def main():
                           dtype=torch.uint8, device=dev)
         out_ = ulsnn.MlpGradResult(torch.empty(W1_.shape, device=dev), torch.empty(W2_.shape, device=dev),
                                    torch.empty(1, device=dev))
-        for _ in range(2):
-            ulsnn.mlp_grad(W1_, W2_, X_, y_, out=out_, workspace=ws_)
-        torch.cuda.synchronize()
+        settle(torch, lambda: ulsnn.mlp_grad(W1_, W2_, X_, y_, out=out_, workspace=ws_), 0.1)
         t1 = time.perf_counter()
         for _ in range(reps):
             ulsnn.mlp_grad(W1_, W2_, X_, y_, out=out_, workspace=ws_)
@@ -293,9 +296,7 @@ def main():
         sws = torch.empty(ulsnn.mlp_grad_workspace_bytes(sm.n_in, sm.n_hid, sm.n_out, 256), dtype=torch.uint8, device=dev)
         sout = ulsnn.MlpGradResult(torch.empty_like(sW1), torch.empty_like(sW2), torch.empty(1, device=dev),
                                    torch.empty_like(sb1), torch.empty_like(sb2))
-        for _ in range(10):
-            ulsnn.mlp_grad(sW1, sW2, sX, sy, sb1, sb2, out=sout, workspace=sws)
-        torch.cuda.synchronize()
+        settle(torch, lambda: ulsnn.mlp_grad(sW1, sW2, sX, sy, sb1, sb2, out=sout, workspace=sws), 0.05)
         t1 = time.perf_counter()
         for _ in range(200):
             ulsnn.mlp_grad(sW1, sW2, sX, sy, sb1, sb2, out=sout, workspace=sws)
