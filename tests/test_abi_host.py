@@ -229,3 +229,15 @@ def test_binding_refuses_cpu_tensors():
     a = torch.zeros(4, 4)
     with pytest.raises(TypeError):
         ulsnn.sgemm("N", "N", 4, 4, 4, 1.0, a, 4, a, 4, 0.0, a, 4)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU only: any other --gpus value ends with a message and a non-zero status before any
+    GPU or library work."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and r.stdout.strip() == ""
+    assert "ONE GPU" in r.stderr and "--gpus 2" in r.stderr
