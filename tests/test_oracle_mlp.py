@@ -182,3 +182,21 @@ def test_empty_batch():
     W1, W2, b1, b2, X, y = _net(4, 3, 2, 1, 3, biases=True)
     g = oracle.mlp_grad(W1, W2, X[:0], y[:0], b1, b2)
     assert g.loss == 0 and not g.dW1.any() and not g.dW2.any() and not g.db1.any() and not g.db2.any()
+
+
+def test_float32_loss_only_form():
+    """The float build of the error-only function: inside float rounding of the double one and of the closed form
+    B ln n_out (W2 = 0), equal to the loss the float gradient function reports (same steps, same order), ignores
+    out-of-range labels, and is not the double arithmetic under another name."""
+    W1, W2, b1, b2, X, y = _net(64, 32, 10, 256, 0, biases=True)
+    l64 = oracle.mlp_loss(W1, W2, X, y, b1, b2)
+    l32 = oracle.mlp_loss(W1, W2, X, y, b1, b2, dtype=np.float32)
+    assert 0 < abs(l32 - l64) < 2e-6 * l64
+    assert l32 == oracle.mlp_grad(W1, W2, X, y, b1, b2, dtype=np.float32).loss
+    flat = oracle.mlp_loss(W1, np.zeros_like(W2), X, y, dtype=np.float32)
+    assert abs(flat - 256 * math.log(10)) < 2e-6 * 256 * math.log(10)
+    y2 = y.copy()
+    y2[::2] = -3
+    kept = oracle.mlp_loss(W1, W2, X[1::2], y[1::2], b1, b2, dtype=np.float32)
+    assert abs(oracle.mlp_loss(W1, W2, X, y2, b1, b2, dtype=np.float32) - kept) < 1e-9 * kept
+    assert oracle.mlp_loss(W1, W2, X[:0], y[:0], b1, b2, dtype=np.float32) == 0.0

@@ -101,3 +101,19 @@ def test_closed_forms_and_float32_form():
     a = oracle.mlp_grad_mse(W1, W2, X[:8], T[:8])
     b = oracle.mlp_grad_mse(W1, W2, X[8:], T[8:])
     assert np.allclose(a.dW2 + b.dW2, g64.dW2, rtol=1e-12, atol=1e-13) and abs(a.loss + b.loss - g64.loss) < 1e-11
+
+
+def test_float32_error_only_form():
+    """The float build of the squared-error evaluation: inside float rounding of the double one and of the closed
+    forms (W2 = 0 gives sum t^2; targets equal to the float outputs give exactly 0), equal to the error the float
+    gradient function reports, and really float arithmetic."""
+    W1, W2, b1, b2, X, T = _net(12, 8, 6, 20, 9, biases=True)
+    e64 = oracle.mlp_mse(W1, W2, X, T, b1, b2)
+    e32 = oracle.mlp_mse(W1, W2, X, T, b1, b2, dtype=np.float32)
+    assert 0 < abs(e32 - e64) < 2e-6 * e64
+    assert e32 == oracle.mlp_grad_mse(W1, W2, X, T, b1, b2, dtype=np.float32).loss
+    t32 = T.astype(np.float32).astype(np.float64)
+    flat = oracle.mlp_mse(W1, np.zeros_like(W2), X, T, dtype=np.float32)
+    assert abs(flat - (t32 ** 2).sum()) < 2e-6 * (t32 ** 2).sum()
+    Y32 = oracle.mlp_grad_mse(W1, W2, X, T, b1, b2, dtype=np.float32, intermediates=True).Y
+    assert oracle.mlp_mse(W1, W2, X, Y32, b1, b2, dtype=np.float32) == 0.0
