@@ -113,10 +113,32 @@ def test_epoch_and_accumulate():
     _compare(out, _oracle(*p), "accumulate 1000+1324")
 
 
+def test_full_size_batch_65536_against_the_oracle():
+    """The bf16 workload at its full size (one internal pass of 65536 patterns, the tile shapes and k splits the
+    benchmark times) against the oracle: the oracle's gradient over 65536 patterns is the float64 sum of its
+    gradients over slices of 512 patterns (additive over patterns, section 4.3)."""
+    shape, n = si.MLP_JOCR, 65536
+    W1, W2, b1, b2, X, y = _problem(shape, 2, n)
+    whole = _gpu(W1, W2, None, None, X, y)
+    torch.cuda.synchronize()
+
+    class Ref:
+        dW1 = np.zeros(W1.shape)
+        dW2 = np.zeros(W2.shape)
+        db1 = db2 = None
+        loss = 0.0
+
+    for r0 in range(0, n, 512):
+        g = _oracle(W1, W2, None, None, X[r0:r0 + 512], y[r0:r0 + 512])
+        Ref.dW1 += g.dW1
+        Ref.dW2 += g.dW2
+        Ref.loss += g.loss
+    _compare(whole, Ref, "400-480-3203 B=65536")
+
+
 def test_full_size_batch_65536_is_the_sum_of_its_parts():
-    """The bf16 workload at full size (one internal pass of 65536 patterns): the oracle cannot run 65536
-    patterns in seconds, so the whole is checked against the double-precision sum of sixteen 4096-pattern
-    gradients from the same path (one of which is checked element by element against the oracle above)."""
+    """The same batch against the double-precision sum of sixteen 4096-pattern gradients from the same path
+    (different tile shapes and k splits; one of them is checked element by element against the oracle above)."""
     shape, n = si.MLP_JOCR, 65536
     W1, W2, _, _ = si.mlp_weights(shape, 2, device=DEV)
     X, y = si.mlp_patterns(shape, 2, 0, n, device=DEV)
