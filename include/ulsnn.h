@@ -54,7 +54,10 @@ typedef enum ulsnn_status {
  *   Products are accumulated in fp32 on the matrix cores; the order of summation is unspecified.
  *   A, B read-only; pointers need only 4-byte alignment.  A or B NULL is an error unless that operand is
  *   never read (m, n == 0, or k == 0, or alpha == 0).
+ *   lda and ldb may not exceed ULSNN_MAX_LD (the kernels keep 32-bit element offsets inside a tile of up to 256
+ *   rows): a larger one returns ULSNN_ERR_UNSUPPORTED.  ldc has no such limit.
  */
+#define ULSNN_MAX_LD (1 << 24)
 int ulsnn_sgemm(char transa, char transb, int m, int n, int k, float alpha, const float *A, int lda,
                 const float *B, int ldb, float beta, float *C, int ldc, void *hip_stream);
 
@@ -77,6 +80,7 @@ int ulsnn_sgemm(char transa, char transb, int m, int n, int k, float alpha, cons
  *                      Fastest when n_in and n_hid are multiples of 8 (16-byte rows); other sizes are correct but
  *                      use an element-wise fetch for the operands whose rows are not 16-byte aligned (W1 and W2
  *                      are re-laid out internally, X is not).  Any other value: ULSNN_ERR_UNSUPPORTED.
+ *   n_in, n_hid and n_out may not exceed ULSNN_MAX_LD (ULSNN_ERR_UNSUPPORTED).
  *   workspace: device scratch of at least ulsnn_mlp_grad_workspace_bytes(desc, batch) bytes, 256-byte aligned.
  *     Its contents on entry do not matter and are undefined on return.  Two calls that may run concurrently
  *     (different streams) need different workspaces.
@@ -121,6 +125,12 @@ size_t ulsnn_mlp_grad_workspace_bytes(const ulsnn_mlp_desc *desc, int batch);
  */
 int ulsnn_mlp_grad(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X,
                    const int32_t *labels, int batch, float *dW1, float *dW2, float *loss);
+
+/*
+ * Debug helper for the label rule above: *count (ONE device int64) = number of labels[0..batch) outside
+ * [0, n_out), i.e. of patterns ulsnn_mlp_grad would ignore.  Asynchronous on hip_stream.  batch == 0 gives 0.
+ */
+int ulsnn_check_labels(const int32_t *labels, int64_t batch, int n_out, int64_t *count, void *hip_stream);
 
 /*
  * Error-only evaluation (forward pass and loss, no gradient): what a line search calls between gradients.
@@ -181,7 +191,8 @@ int ulsnn_mlp_grad_timed(const ulsnn_mlp_desc *desc, const void *W1, const void 
 /*
  * Host-only diagnostic: writes to buf (NUL-terminated, truncated to buf_bytes) one line per matrix product of
  * the gradient (section 4.2) with the tile shape, tile grid, k split and modelled time this build would use
- * for `batch` patterns (for the first internal pass if the batch is processed in several).  The first line also
+ * for `batch` patterns: for the first internal pass if the batch is processed in several, followed, when the last
+ * pass is shorter, by a line "tail_rows=R" and the five lines of that pass.  The first line also
  * says whether the call would take the two-launch path for small networks instead (small_network_path=1: nets up
  * to 128-64-64 at up to 4096 patterns, softmax form, fp32).  Launches nothing.
  */

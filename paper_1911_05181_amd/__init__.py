@@ -29,6 +29,7 @@ from .binding import (  # noqa: F401
     mlp_grad_timed,
     MLP_STAGES,
     mlp_grad_workspace_bytes,
+    check_labels,
     sgemm,
     sgemm_flops,
     status_string,

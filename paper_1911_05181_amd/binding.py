@@ -60,6 +60,8 @@ def load():
     L.ulsnn_mlp_grad_workspace_bytes.restype = C.c_size_t
     L.ulsnn_mlp_grad.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, i, vp, vp, vp]
     L.ulsnn_mlp_grad.restype = i
+    L.ulsnn_check_labels.argtypes = [vp, C.c_int64, i, vp, vp]
+    L.ulsnn_check_labels.restype = i
     L.ulsnn_mlp_grad_epoch.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, C.c_int64, i, vp, vp, vp]
     L.ulsnn_mlp_grad_epoch.restype = i
     L.ulsnn_mlp_grad_timed.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, i, vp, vp, vp, C.POINTER(C.c_float)]
@@ -132,27 +134,81 @@ def _stream(stream) -> C.c_void_p:
     return C.c_void_p(stream.cuda_stream)
 
 
+def _on_gpu(t) -> bool:
+    return isinstance(t, torch.Tensor) and t.is_cuda
+
+
 def _dev_f32(t: torch.Tensor, name: str):
-    if not (t.is_cuda and t.dtype == torch.float32):
+    if not (_on_gpu(t) and t.dtype == torch.float32):
         raise TypeError(f"{name} must be a float32 tensor on the GPU")
+
+
+def _dense_f32(t: torch.Tensor, name: str, numel: int = None, shape=None):
+    """A contiguous float32 GPU tensor, optionally of a given element count or shape."""
+    _dev_f32(t, name)
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be dense (contiguous)")
+    if numel is not None and t.numel() != numel:
+        raise ValueError(f"{name} must hold {numel} elements, not {t.numel()}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, not {tuple(t.shape)}")
+
+
+def _workspace(workspace, need: int, device, stream):
+    """The caller's workspace (checked), or a fresh one.  A fresh one is handed to torch's caching allocator
+    again when this function's caller returns, while the kernels that use it may still be queued: that is safe on
+    the current stream (same-stream reuse is ordered) and, with record_stream, on any other stream."""
+    if workspace is not None:
+        if not (_on_gpu(workspace) and workspace.is_contiguous()):
+            raise TypeError("workspace must be a contiguous GPU tensor")
+        return workspace
+    workspace = torch.empty(max(int(need), 256), dtype=torch.uint8, device=device)
+    if stream is not None:
+        workspace.record_stream(stream)
+    return workspace
+
+
+def _check_gemm_operand(t, name, rows, cols, ld):
+    """The stored matrix (rows x cols, row stride ld) must lie inside the tensor."""
+    if rows <= 0 or cols <= 0:
+        return
+    if t is None:
+        raise ValueError(f"{name} is missing")
+    if ld < cols:
+        return                      # the library reports the leading-dimension error
+    if (rows - 1) * ld + cols > t.numel():
+        raise ValueError(f"{name}: {rows} x {cols} with leading dimension {ld} needs "
+                         f"{(rows - 1) * ld + cols} elements, the tensor holds {t.numel()}")
+
+
+def _check_sgemm_tensors(transa, transb, m, n, k, alpha, A, lda, B, ldb, Cmat, ldc):
+    """Types, and that every element the product touches lies inside its tensor (the library cannot know the
+    size of the memory behind a pointer).  Flags and sizes themselves are checked by the library."""
+    for t, nm in ((A, "A"), (B, "B"), (Cmat, "C")):
+        if t is not None:
+            _dense_f32(t, nm)
+    if min(m, n, k) < 0 or str(transa)[:1] not in "NnTtCc" or str(transb)[:1] not in "NnTtCc":
+        return
+    _check_gemm_operand(Cmat, "C", m, n, ldc)
+    if m > 0 and n > 0 and k > 0 and alpha != 0.0:
+        a_rows, a_cols = (m, k) if str(transa)[:1] in "Nn" else (k, m)
+        b_rows, b_cols = (k, n) if str(transb)[:1] in "Nn" else (n, k)
+        _check_gemm_operand(A, "A", a_rows, a_cols, lda)
+        _check_gemm_operand(B, "B", b_rows, b_cols, ldb)
 
 
 def sgemm(transa: str, transb: str, m: int, n: int, k: int, alpha: float, A: torch.Tensor, lda: int,
           B: torch.Tensor, ldb: int, beta: float, Cmat: torch.Tensor, ldc: int, stream=None) -> None:
     """C = alpha*op(A)*op(B) + beta*C in place on the GPU (row-major, BLAS SGEMM argument order)."""
-    for t, nm in ((A, "A"), (B, "B"), (Cmat, "C")):
-        if t is not None:
-            _dev_f32(t, nm)
+    _check_sgemm_tensors(transa, transb, m, n, k, alpha, A, lda, B, ldb, Cmat, ldc)
     rc = load().ulsnn_sgemm(transa.encode()[:1], transb.encode()[:1], m, n, k, alpha, _ptr(A), lda, _ptr(B), ldb,
                             beta, _ptr(Cmat), ldc, _stream(stream))
     if rc:
         raise UlsnnError(rc, "ulsnn_sgemm")
 
 
-def _vec_ws(workspace, device):
-    if workspace is None:
-        workspace = torch.empty(VEC_WORKSPACE_BYTES, dtype=torch.uint8, device=device)
-    return workspace
+def _vec_ws(workspace, device, stream=None):
+    return _workspace(workspace, VEC_WORKSPACE_BYTES, device, stream)
 
 
 def dot(x: torch.Tensor, y: torch.Tensor, *, out: Optional[torch.Tensor] = None, workspace=None, stream=None):
@@ -162,7 +218,7 @@ def dot(x: torch.Tensor, y: torch.Tensor, *, out: Optional[torch.Tensor] = None,
         raise ValueError("dot: contiguous tensors of equal size")
     if out is None:
         out = torch.empty(1, device=x.device)
-    workspace = _vec_ws(workspace, x.device)
+    workspace = _vec_ws(workspace, x.device, stream)
     rc = load().ulsnn_dot(x.numel(), _ptr(x), _ptr(y), _ptr(out), _ptr(workspace), workspace.numel(), _stream(stream))
     if rc:
         raise UlsnnError(rc, "ulsnn_dot")
@@ -191,7 +247,7 @@ def cg_direction(g_new: torch.Tensor, g_old: Optional[torch.Tensor], d: torch.Te
             raise ValueError("cg_direction: contiguous tensors of equal size")
     if beta is None:
         beta = torch.empty(1, device=d.device)
-    workspace = _vec_ws(workspace, d.device)
+    workspace = _vec_ws(workspace, d.device, stream)
     rc = load().ulsnn_cg_direction(g_new.numel(), _ptr(g_new), _ptr(g_old), _ptr(d), _ptr(beta), _ptr(workspace),
                                    workspace.numel(), _stream(stream))
     if rc:
@@ -213,9 +269,7 @@ def mlp_line_search(W1, W2, d1, d2, X, labels, bracket_batch: int, alpha0: float
         if t.shape != ref.shape or not t.is_contiguous():
             raise ValueError(f"{nm} must be contiguous and shaped like its weight matrix")
     batch = X.shape[0]
-    if workspace is None:
-        workspace = torch.empty(max(mlp_line_search_workspace_bytes(n_in, n_hid, n_out, batch), 256), dtype=torch.uint8,
-                                device=W1.device)
+    workspace = _workspace(workspace, mlp_line_search_workspace_bytes(n_in, n_hid, n_out, batch), W1.device, stream)
     d = _desc(n_in, n_hid, n_out, None, None, None, None, False, workspace, stream, odt)
     res = LineSearchResult()
     rc = load().ulsnn_mlp_line_search(C.byref(d), _ptr(W1), _ptr(W2), _ptr(d1), _ptr(d2), _ptr(X), _ptr(labels), batch,
@@ -232,11 +286,9 @@ def sgemm_planned(tile_shape: int, k_splits: int, transa: str, transb: str, m: i
                   A: torch.Tensor, lda: int, B: torch.Tensor, ldb: int, beta: float, Cmat: torch.Tensor, ldc: int,
                   workspace: Optional[torch.Tensor] = None, stream=None) -> None:
     """ulsnn_sgemm_planned: SGEMM with the tile shape and k split chosen by the caller."""
-    for t, nm in ((A, "A"), (B, "B"), (Cmat, "C")):
-        if t is not None:
-            _dev_f32(t, nm)
-    if workspace is None and k_splits > 1:
-        workspace = torch.empty(max(k_splits * m * n * 4, 256), dtype=torch.uint8, device=Cmat.device)
+    _check_sgemm_tensors(transa, transb, m, n, k, alpha, A, lda, B, ldb, Cmat, ldc)
+    if k_splits > 1 and m > 0 and n > 0 and Cmat is not None:
+        workspace = _workspace(workspace, k_splits * m * n * 4, Cmat.device, stream)
     rc = load().ulsnn_sgemm_planned(tile_shape, k_splits, transa.encode()[:1], transb.encode()[:1], m, n, k, alpha,
                                     _ptr(A), lda, _ptr(B), ldb, beta, _ptr(Cmat), ldc, _ptr(workspace),
                                     0 if workspace is None else workspace.numel() * workspace.element_size(),
@@ -300,7 +352,7 @@ def _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate, dense_targets=False)
     int32 label vector, or with dense_targets the float32 target matrix [batch x n_out]."""
     if W1.dtype == torch.bfloat16:
         for t, nm in ((W1, "W1"), (W2, "W2"), (X, "X")):
-            if not (t.is_cuda and t.dtype == torch.bfloat16):
+            if not (_on_gpu(t) and t.dtype == torch.bfloat16):
                 raise TypeError(f"{nm} must be a bfloat16 tensor on the GPU (W1 is bfloat16)")
         operand_dtype = 1
     else:
@@ -310,7 +362,7 @@ def _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate, dense_targets=False)
         _dev_f32(labels, "T")
         if labels.dim() != 2 or labels.shape[1] != W2.shape[1]:
             raise ValueError("T must be [batch x n_out]")
-    elif not (labels.is_cuda and labels.dtype == torch.int32):
+    elif not (_on_gpu(labels) and labels.dtype == torch.int32):
         raise TypeError("labels must be an int32 tensor on the GPU")
     for t in (W1, W2, X, labels):
         if not t.is_contiguous():
@@ -321,6 +373,20 @@ def _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate, dense_targets=False)
         raise ValueError("shape mismatch between W1, W2, X and labels")
     if (b1 is None) != (b2 is None):
         raise ValueError("give both biases or neither")
+    if b1 is not None:
+        _dense_f32(b1, "b1", numel=n_hid)
+        _dense_f32(b2, "b2", numel=n_out)
+    if out is not None:
+        if out.dW1 is not None or out.dW2 is not None:
+            _dense_f32(out.dW1, "out.dW1", shape=W1.shape)
+            _dense_f32(out.dW2, "out.dW2", shape=W2.shape)
+        if out.loss is not None:
+            _dense_f32(out.loss, "out.loss", numel=1)
+        if b1 is not None and out.dW1 is not None:
+            if out.db1 is None or out.db2 is None:
+                raise ValueError("out.db1 and out.db2 are needed when biases are given")
+            _dense_f32(out.db1, "out.db1", numel=n_hid)
+            _dense_f32(out.db2, "out.db2", numel=n_out)
     if out is None:
         if accumulate:
             raise ValueError("accumulate=True needs the tensors to add to (out=...)")
@@ -337,14 +403,26 @@ def mlp_grad(W1, W2, X, labels, b1=None, b2=None, *, out: Optional[MlpGradResult
     """Loss and gradient of the MLP summed over the rows of X (ulsnn_mlp_grad).  Asynchronous on the stream."""
     n_in, n_hid, n_out, out, odt = _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate)
     batch = X.shape[0]
-    if workspace is None:
-        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch, odt)
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
+    workspace = _workspace(workspace, mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch, odt), W1.device, stream)
     d = _desc(n_in, n_hid, n_out, b1, b2, out.db1, out.db2, accumulate, workspace, stream, odt)
     rc = load().ulsnn_mlp_grad(C.byref(d), _ptr(W1), _ptr(W2), _ptr(X), _ptr(labels), batch, _ptr(out.dW1),
                                _ptr(out.dW2), _ptr(out.loss))
     if rc:
         raise UlsnnError(rc, "ulsnn_mlp_grad")
+    return out
+
+
+def check_labels(labels: torch.Tensor, n_out: int, *, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Number of labels outside [0, n_out) as a one-element int64 device tensor (ulsnn_check_labels)."""
+    if not (_on_gpu(labels) and labels.dtype == torch.int32 and labels.is_contiguous()):
+        raise TypeError("labels must be a contiguous int32 tensor on the GPU")
+    if out is None:
+        out = torch.empty(1, dtype=torch.int64, device=labels.device)
+    elif not (_on_gpu(out) and out.dtype == torch.int64 and out.numel() == 1):
+        raise TypeError("out must be a one-element int64 tensor on the GPU")
+    rc = load().ulsnn_check_labels(_ptr(labels), labels.numel(), n_out, _ptr(out), _stream(stream))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_check_labels")
     return out
 
 
@@ -356,9 +434,9 @@ def _loss_only(entry, W1, W2, X, targets, b1, b2, loss, accumulate, workspace, s
         if accumulate:
             raise ValueError("accumulate=True needs the tensor to add to (loss=...)")
         loss = torch.empty(1, device=W1.device)
-    if workspace is None:
-        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch, odt)
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
+    else:
+        _dense_f32(loss, "loss", numel=1)
+    workspace = _workspace(workspace, mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch, odt), W1.device, stream)
     d = _desc(n_in, n_hid, n_out, b1, b2, None, None, accumulate, workspace, stream, odt)
     rc = getattr(load(), entry)(C.byref(d), _ptr(W1), _ptr(W2), _ptr(X), _ptr(targets), batch, _ptr(loss))
     if rc:
@@ -381,9 +459,7 @@ def mlp_grad_mse(W1, W2, X, T, b1=None, b2=None, *, out: Optional[MlpGradResult]
     """Squared error of the tanh-output network and its gradient (ulsnn_mlp_grad_mse), the paper's own form."""
     n_in, n_hid, n_out, out, odt = _mlp_common(W1, W2, X, T, b1, b2, out, accumulate, dense_targets=True)
     batch = X.shape[0]
-    if workspace is None:
-        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch, odt)
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
+    workspace = _workspace(workspace, mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch, odt), W1.device, stream)
     d = _desc(n_in, n_hid, n_out, b1, b2, out.db1, out.db2, accumulate, workspace, stream, odt)
     rc = load().ulsnn_mlp_grad_mse(C.byref(d), _ptr(W1), _ptr(W2), _ptr(X), _ptr(T), batch, _ptr(out.dW1),
                                    _ptr(out.dW2), _ptr(out.loss))
@@ -402,9 +478,7 @@ def mlp_grad_timed(W1, W2, X, labels, b1=None, b2=None, *, out: Optional[MlpGrad
     Returns (result, {stage name: milliseconds})."""
     n_in, n_hid, n_out, out, odt = _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate)
     batch = X.shape[0]
-    if workspace is None:
-        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch, odt)
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
+    workspace = _workspace(workspace, mlp_grad_workspace_bytes(n_in, n_hid, n_out, batch, odt), W1.device, stream)
     d = _desc(n_in, n_hid, n_out, b1, b2, out.db1, out.db2, accumulate, workspace, stream, odt)
     ms = (C.c_float * len(MLP_STAGES))()
     rc = load().ulsnn_mlp_grad_timed(C.byref(d), _ptr(W1), _ptr(W2), _ptr(X), _ptr(labels), batch, _ptr(out.dW1),
@@ -419,9 +493,8 @@ def mlp_grad_epoch(W1, W2, X, labels, chunk: int, b1=None, b2=None, *, out: Opti
     """Gradient over all rows of X taken `chunk` patterns at a time and summed (ulsnn_mlp_grad_epoch)."""
     n_in, n_hid, n_out, out, odt = _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate)
     n = X.shape[0]
-    if workspace is None:
-        need = mlp_grad_workspace_bytes(n_in, n_hid, n_out, min(max(chunk, 1), max(n, 1)), odt)
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=W1.device)
+    workspace = _workspace(workspace, mlp_grad_workspace_bytes(n_in, n_hid, n_out, min(max(chunk, 1), max(n, 1)), odt),
+                           W1.device, stream)
     d = _desc(n_in, n_hid, n_out, b1, b2, out.db1, out.db2, accumulate, workspace, stream, odt)
     rc = load().ulsnn_mlp_grad_epoch(C.byref(d), _ptr(W1), _ptr(W2), _ptr(X), _ptr(labels), n, chunk,
                                      _ptr(out.dW1), _ptr(out.dW2), _ptr(out.loss))

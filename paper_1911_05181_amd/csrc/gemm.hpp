@@ -45,19 +45,7 @@ struct GemmArgs {
     int kchunk;          // k range handled per blockIdx.y (multiple of BK); >= K when there is no split
     int tiles_m, tiles_n;
     size_t partial_stride;  // EPI_PARTIAL: elements between consecutive partial results
-#ifdef ULSNN_TRACE
-    long long *trace;       // diagnostic builds only: 8 timestamps/ids per workgroup
-#endif
 };
-
-#ifdef ULSNN_TRACE
-#define ULSNN_STAMP(slot)                                                                              \
-    do {                                                                                               \
-        if (g.trace && threadIdx.x == 0) g.trace[(size_t)wg_linear * 8 + (slot)] = wall_clock64();     \
-    } while (0)
-#else
-#define ULSNN_STAMP(slot) do { } while (0)
-#endif
 
 // WAVES_PER_SIMD_ is the occupancy the register allocation must allow (wavefronts per SIMD).
 // KW_ > 1: KW_ groups of WM x WN wavefronts share the tile; each group takes 1/KW_ of every k step and the
@@ -361,8 +349,7 @@ constexpr int gemm_lds_floats()
 // aligned LDS; every thread of the workgroup must call this, and LDS is free again on return.
 template <class Cfg, bool A_KC, bool B_KC, int EPI>
 __device__ __forceinline__ void gemm_segment(const GemmArgs &g, const int tile_m, const int tile_n, const int kbeg,
-                                             const int kend, float *Cout, const int ldc, float *lds,
-                                             const int wg_linear)
+                                             const int kend, float *Cout, const int ldc, float *lds)
 {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, THREADS = Cfg::THREADS;
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
@@ -370,7 +357,6 @@ __device__ __forceinline__ void gemm_segment(const GemmArgs &g, const int tile_m
     using PB = Panel<B_KC, BN, BK>;
     constexpr int NVA = (BM * BK / 4 + THREADS - 1) / THREADS;
     constexpr int NVB = (BN * BK / 4 + THREADS - 1) / THREADS;
-    (void)wg_linear;
 
     auto stage_a = [&](int st) { return lds + st * PA::SIZE; };
     auto stage_b = [&](int st) { return lds + 2 * PA::SIZE + st * PB::SIZE; };
@@ -384,17 +370,6 @@ __device__ __forceinline__ void gemm_segment(const GemmArgs &g, const int tile_m
     const int wrow = wm * Cfg::WTM, wcol = wn * Cfg::WTN;
 
     const int i0 = tile_m * BM, j0 = tile_n * BN;
-    ULSNN_STAMP(0);
-#ifdef ULSNN_TRACE
-    if (g.trace && threadIdx.x == 0) {
-        unsigned hwid, xcc;
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-        g.trace[(size_t)wg_linear * 8 + 4] = hwid;
-        g.trace[(size_t)wg_linear * 8 + 5] = xcc;
-        g.trace[(size_t)wg_linear * 8 + 6] = clock64();
-    }
-#endif
     const int nfull = (kend - kbeg) / BK;             // steps fetched without any check
     const bool tail = (kend - kbeg) % BK != 0;        // one last, partial step: checked fetch, zero filled
     const int nkb = nfull + (tail ? 1 : 0);
@@ -441,7 +416,6 @@ __device__ __forceinline__ void gemm_segment(const GemmArgs &g, const int tile_m
         panel_store<B_KC, BN, BK, THREADS, NVB>(stage_b(0), rb, tid);
     }
     __syncthreads();
-    ULSNN_STAMP(1);
 
     // All matrix-core work of one step on LDS stage `cur`.  Several workgroups share a compute unit, so the
     // latency of these LDS reads is covered by the products of the other workgroups' wavefronts.
@@ -488,7 +462,6 @@ __device__ __forceinline__ void gemm_segment(const GemmArgs &g, const int tile_m
         __syncthreads();
     }
 
-    ULSNN_STAMP(2);
     if (Cfg::KW > 1) {
         // The k loop ended with a barrier, so the panels are dead: groups 1.. park their accumulators in LDS
         // (one 64-lane row per register: conflict free), group 0 adds them in group order and goes on alone.
@@ -549,16 +522,11 @@ __device__ __forceinline__ void gemm_segment(const GemmArgs &g, const int tile_m
             }
         }
     }
-    ULSNN_STAMP(3);
-#ifdef ULSNN_TRACE
-    if (g.trace && threadIdx.x == 0) g.trace[(size_t)wg_linear * 8 + 7] = clock64();
-#endif
 }
 
 // The work of one workgroup: `hw` is its position in the launch order of this problem's tiles x splits workgroups.
 template <class Cfg, bool A_KC, bool B_KC, int EPI>
-__device__ __forceinline__ void gemm_tile(const GemmArgs &g, const int hw, const int splits, float *lds,
-                                          const int wg_linear)
+__device__ __forceinline__ void gemm_tile(const GemmArgs &g, const int hw, const int splits, float *lds)
 {
     int tile_m, tile_n, z;
     work_of_workgroup(hw, g.tiles_m, g.tiles_n, splits, tile_m, tile_n, z);
@@ -570,7 +538,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &g, const int hw, const
         Cout = g.C + (size_t)z * g.partial_stride;
         ldc = g.N;
     }
-    gemm_segment<Cfg, A_KC, B_KC, EPI>(g, tile_m, tile_n, kbeg, kend, Cout, ldc, lds, wg_linear);
+    gemm_segment<Cfg, A_KC, B_KC, EPI>(g, tile_m, tile_n, kbeg, kend, Cout, ldc, lds);
 }
 
 // One GEMM per launch: grid = (tiles, k splits).
@@ -579,7 +547,7 @@ __global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm_kernel
 {
     __shared__ __attribute__((aligned(16))) float lds[gemm_lds_floats<Cfg, A_KC, B_KC>()];
     const int hw = blockIdx.y * gridDim.x + blockIdx.x;
-    gemm_tile<Cfg, A_KC, B_KC, EPI>(g, hw, gridDim.y, lds, hw);
+    gemm_tile<Cfg, A_KC, B_KC, EPI>(g, hw, gridDim.y, lds);
 }
 
 // Two independent GEMMs in one launch (1-D grid): workgroups [0, n1) work on g1, the rest on g2.  The second
@@ -595,10 +563,10 @@ void gemm_pair_kernel(const GemmArgs g1, const GemmArgs g2, const int n1)
     __shared__ __attribute__((aligned(16))) float lds[L1 > L2 ? L1 : L2];
     const int id = blockIdx.x;
     if (id < n1) {
-        gemm_tile<Cfg1, A_KC1, B_KC1, EPI1>(g1, id, n1 / (g1.tiles_m * g1.tiles_n), lds, id);
+        gemm_tile<Cfg1, A_KC1, B_KC1, EPI1>(g1, id, n1 / (g1.tiles_m * g1.tiles_n), lds);
     } else {
         const int n2 = gridDim.x - n1;
-        gemm_tile<Cfg2, A_KC2, B_KC2, EPI2>(g2, id - n1, n2 / (g2.tiles_m * g2.tiles_n), lds, id);
+        gemm_tile<Cfg2, A_KC2, B_KC2, EPI2>(g2, id - n1, n2 / (g2.tiles_m * g2.tiles_n), lds);
     }
 }
 

@@ -264,6 +264,27 @@ __global__ __launch_bounds__(1024) void loss_reduce_kernel(const float *__restri
     }
 }
 
+// *count = number of labels outside [0, n_out): the patterns the output stage ignores.  One workgroup.
+__global__ __launch_bounds__(1024) void count_ignored_labels_kernel(const int32_t *__restrict__ labels, long long n,
+                                                                    int n_out, long long *__restrict__ count)
+{
+    __shared__ long long red[16];
+    long long c = 0;
+    for (long long r = threadIdx.x; r < n; r += 1024) {
+        const int y = labels[r];
+        c += (y < 0 || y >= n_out) ? 1 : 0;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long t = 0;
+        for (int w = 0; w < 16; ++w) t += red[w];
+        *count = t;
+    }
+}
+
 // Fill n floats with zero (used instead of a memset so that the call can be captured in a HIP graph).
 __global__ __launch_bounds__(256) void zero_kernel(float *__restrict__ p, size_t n)
 {

@@ -19,11 +19,24 @@ using namespace ulsnn;
 
 namespace {
 
-constexpr int NUM_CU = 256;          // MI355X: 8 XCDs x 32 compute units
-#ifndef ULSNN_SLAB_ROWS
-#define ULSNN_SLAB_ROWS 65536
-#endif
-constexpr int SLAB_ROWS = ULSNN_SLAB_ROWS;   // patterns processed per internal pass of the MLP gradient
+// Compute units of the current device (MI355X: 8 XCDs x 32 = 256), read from the runtime once; the planner's
+// cost model and the grid sizes of the streaming kernels use it.  Without a device (host-only plan queries) the
+// MI355X figure is assumed.
+int query_num_cu()
+{
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+        return n;
+    (void)hipGetLastError();   // no device: not an error of a later launch
+    return 256;
+}
+inline int num_cu()
+{
+    static const int n = query_num_cu();
+    return n;
+}
+constexpr int SLAB_ROWS = 65536;     // patterns processed per internal pass of the MLP gradient
 
 inline bool is_n(char t) { return t == 'N' || t == 'n'; }
 inline bool is_t(char t) { return t == 'T' || t == 't' || t == 'C' || t == 'c'; }
@@ -101,14 +114,14 @@ double model_us(const CfgInfo &c, bool a_kc, bool b_kc, int m, int n, int k, int
     const long tiles = (long)((m + c.bm - 1) / c.bm) * ((n + c.bn - 1) / c.bn);
     const long wgs = tiles * sp;
     const double layout = (!a_kc && !b_kc) ? 0.92 : (a_kc && b_kc) ? 1.0 : 0.97;   // 4-byte LDS reads cost more
-    const double cu_rate = peak_flops / NUM_CU * c.eff * layout;                   // flop/s of one compute unit
+    const double cu_rate = peak_flops / 256.0 * c.eff * layout;   // flop/s of one compute unit (peak is for 256 of them)
     const double flops_wg = 2.0 * c.bm * c.bn * (double)chunk;
     const double wps = c.threads / 256.0;                                          // wavefronts per SIMD per WG
-    const long slots = (long)NUM_CU * c.occ;
+    const long slots = (long)num_cu() * c.occ;
     const long full = wgs / slots, rem = wgs % slots;
     double t = full * c.occ * flops_wg / (cu_rate * simd_utilisation(c.occ * wps));
     if (rem) {
-        const double per_cu = std::ceil((double)rem / NUM_CU);
+        const double per_cu = std::ceil((double)rem / num_cu());
         t += per_cu * flops_wg / (cu_rate * simd_utilisation(per_cu * wps));
     }
     t += 3.0e-6 + (double)m * n * sp * 4.0 / 4.0e12;                               // ramp-up and the store burst
@@ -150,10 +163,10 @@ GemmPlan plan_gemm(int m, int n, int k, bool a_kc, bool b_kc, int split_limit, u
     if (best.cfg == CFG_64 && best.splits == 1) {
         const long tiles = (long)best.tiles_m * best.tiles_n;
         CfgId alt = CFG_64;
-        if ((cfg_mask >> CFG_64K32 & 1) && tiles <= 4 * NUM_CU && k >= 4 * CFG_INFO[CFG_64K32].bk &&
+        if ((cfg_mask >> CFG_64K32 & 1) && tiles <= 4 * num_cu() && k >= 4 * CFG_INFO[CFG_64K32].bk &&
             k % CFG_INFO[CFG_64K32].bk == 0)   // (a partial last step would eat the gain: hidden layer, k = 400)
             alt = CFG_64K32;
-        if ((cfg_mask >> CFG_64K64 & 1) && tiles <= NUM_CU && k >= 4 * CFG_INFO[CFG_64K64].bk) alt = CFG_64K64;
+        if ((cfg_mask >> CFG_64K64 & 1) && tiles <= num_cu() && k >= 4 * CFG_INFO[CFG_64K64].bk) alt = CFG_64K64;
         if (alt != CFG_64) {
             best.cfg = alt;
             best.kchunk = (int)round_up((size_t)k, CFG_INFO[alt].bk);
@@ -253,7 +266,7 @@ hipError_t launch_pair_partial(const GemmPlan &p4, GemmArgs a4, const GemmPlan &
 
 inline unsigned grid_for(size_t elems)
 {
-    return (unsigned)std::min<size_t>((elems + 255) / 256, (size_t)NUM_CU * 8);
+    return (unsigned)std::min<size_t>((elems + 255) / 256, (size_t)num_cu() * 8);
 }
 
 // The reduction that follows a split-k launch: out = epilogue(sum of partials).
@@ -297,7 +310,7 @@ __global__ __launch_bounds__(256, Cfg::WAVES_PER_SIMD) void dw1_with_tail_kernel
     __shared__ __attribute__((aligned(16))) float lds[gemm_lds_floats<Cfg, false, false>()];
     const int id = blockIdx.x;
     if (id < n_gemm) {
-        gemm_tile<Cfg, false, false, EPI_PARTIAL>(g, id, n_gemm / (g.tiles_m * g.tiles_n), lds, id);
+        gemm_tile<Cfg, false, false, EPI_PARTIAL>(g, id, n_gemm / (g.tiles_m * g.tiles_n), lds);
     } else if (id < n_gemm + t.reduce_blocks) {
         const size_t total = (size_t)t.M * t.N;
         for (size_t idx = (size_t)(id - n_gemm) * 256 + threadIdx.x; idx < total; idx += (size_t)t.reduce_blocks * 256) {
@@ -537,6 +550,7 @@ int check_mlp_args(const ulsnn_mlp_desc *d, const void *W1, const void *W2, cons
 {
     if (!d) return ULSNN_ERR_NULL;
     if (d->n_in < 1 || d->n_hid < 1 || d->n_out < 1 || batch < 0) return ULSNN_ERR_DIM;
+    if (d->n_in > ULSNN_MAX_LD || d->n_hid > ULSNN_MAX_LD || d->n_out > ULSNN_MAX_LD) return ULSNN_ERR_UNSUPPORTED;
     if (!W1 || !W2 || !loss) return ULSNN_ERR_NULL;
     if (backward && (!dW1 || !dW2)) return ULSNN_ERR_NULL;
     if (batch > 0 && (!X || !targets)) return ULSNN_ERR_NULL;
@@ -927,6 +941,7 @@ int ulsnn_sgemm(char transa, char transb, int m, int n, int k, float alpha, cons
     const int cols_a = is_n(transa) ? k : m;
     const int cols_b = is_n(transb) ? n : k;
     if (lda < std::max(1, cols_a) || ldb < std::max(1, cols_b) || ldc < std::max(1, n)) return ULSNN_ERR_LD;
+    if (lda > ULSNN_MAX_LD || ldb > ULSNN_MAX_LD) return ULSNN_ERR_UNSUPPORTED;   // 32-bit offsets inside a tile
     if (m == 0 || n == 0) return ULSNN_OK;
     if (!C) return ULSNN_ERR_NULL;
     hipStream_t s = (hipStream_t)hip_stream;
@@ -957,6 +972,15 @@ int ulsnn_mlp_grad(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, c
     if (rc != ULSNN_OK) return rc;
     return mlp_grad_impl(desc, W1, W2, X, MlpTask{labels, nullptr, true}, batch, dW1, dW2, loss,
                          desc->accumulate != 0);
+}
+
+int ulsnn_check_labels(const int32_t *labels, int64_t batch, int n_out, int64_t *count, void *hip_stream)
+{
+    if (batch < 0 || n_out < 1) return ULSNN_ERR_DIM;
+    if (!count || (batch > 0 && !labels)) return ULSNN_ERR_NULL;
+    hipLaunchKernelGGL(count_ignored_labels_kernel, dim3(1), dim3(1024), 0, (hipStream_t)hip_stream, labels,
+                       (long long)batch, n_out, (long long *)count);
+    return hipGetLastError() == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
 }
 
 int ulsnn_mlp_loss(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X,
@@ -1254,18 +1278,27 @@ int ulsnn_mlp_grad_describe_plan(const ulsnn_mlp_desc *desc, int batch, char *bu
     if (!desc || !buf) return ULSNN_ERR_NULL;
     if (!desc_ok(desc) || batch < 1 || buf_bytes < 1) return ULSNN_ERR_DIM;
     const MlpLayout L = mlp_layout(desc, batch);
-    const SlabPlans P = plan_slab(L, desc->n_in, desc->n_hid, desc->n_out, L.slab);
-    const GemmPlan *g[5] = {&P.g1, &P.g2, &P.g3, &P.g4, &P.g5};
     const char *what[5] = {"hidden_layer", "output_layer", "dW2", "hidden_delta", "dW1"};
     size_t used = 0;
-    int n = snprintf(buf, buf_bytes, "rows_per_pass=%d paired_backward=%d workspace_bytes=%zu small_network_path=%d\n",
-                     L.slab, (int)P.paired, L.bytes, (int)small_net_shape(desc, batch));
-    if (n > 0) used = std::min((size_t)n, buf_bytes - 1);
-    for (int i = 0; i < 5 && used + 1 < buf_bytes; ++i) {
-        n = snprintf(buf + used, buf_bytes - used, "%s: tile=%s tiles=%dx%d splits=%d kchunk=%d model_us=%.1f\n",
-                     what[i], CFG_INFO[g[i]->cfg].name, g[i]->tiles_m, g[i]->tiles_n, g[i]->splits, g[i]->kchunk,
-                     g[i]->est_us);
+    auto add = [&](int n) {
         if (n > 0) used = std::min(used + (size_t)n, buf_bytes - 1);
+    };
+    auto five_lines = [&](const SlabPlans &P) {
+        const GemmPlan *g[5] = {&P.g1, &P.g2, &P.g3, &P.g4, &P.g5};
+        for (int i = 0; i < 5 && used + 1 < buf_bytes; ++i)
+            add(snprintf(buf + used, buf_bytes - used, "%s: tile=%s tiles=%dx%d splits=%d kchunk=%d model_us=%.1f\n",
+                         what[i], CFG_INFO[g[i]->cfg].name, g[i]->tiles_m, g[i]->tiles_n, g[i]->splits, g[i]->kchunk,
+                         g[i]->est_us));
+    };
+    const SlabPlans P = plan_slab(L, desc->n_in, desc->n_hid, desc->n_out, L.slab);
+    add(snprintf(buf, buf_bytes, "rows_per_pass=%d paired_backward=%d workspace_bytes=%zu small_network_path=%d\n",
+                 L.slab, (int)P.paired, L.bytes, (int)small_net_shape(desc, batch)));
+    five_lines(P);
+    const int tail = batch % L.slab;
+    if (tail != 0 && used + 1 < buf_bytes) {
+        const SlabPlans T = plan_slab(L, desc->n_in, desc->n_hid, desc->n_out, tail);
+        add(snprintf(buf + used, buf_bytes - used, "tail_rows=%d paired_backward=%d\n", tail, (int)T.paired));
+        five_lines(T);
     }
     return ULSNN_OK;
 }
@@ -1290,6 +1323,7 @@ int ulsnn_sgemm_planned(int tile_shape, int k_splits, char transa, char transb, 
     const int cols_a = is_n(transa) ? k : m;
     const int cols_b = is_n(transb) ? n : k;
     if (lda < std::max(1, cols_a) || ldb < std::max(1, cols_b) || ldc < std::max(1, n)) return ULSNN_ERR_LD;
+    if (lda > ULSNN_MAX_LD || ldb > ULSNN_MAX_LD) return ULSNN_ERR_UNSUPPORTED;
     if (m == 0 || n == 0) return ULSNN_OK;
     if (!C) return ULSNN_ERR_NULL;
     hipStream_t s = (hipStream_t)hip_stream;

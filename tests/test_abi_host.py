@@ -241,3 +241,95 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0 and r.stdout.strip() == ""
     assert "ONE GPU" in r.stderr and "--gpus 2" in r.stderr
+
+
+def test_leading_dimension_and_network_size_limits():
+    """Kernels keep 32-bit element offsets inside a tile of up to 256 rows, so lda / ldb (and the network
+    dimensions, which become leading dimensions) above ULSNN_MAX_LD are refused before anything is launched."""
+    L = ulsnn.load()
+    max_ld = 1 << 24
+    assert 255 * max_ld + 64 < 1 << 32      # what the limit protects: row 255 of a tile, plus a k step
+    assert _sgemm("N", "N", 4, 5, 6, max_ld + 1, 5, 5) == E_UNSUP
+    assert _sgemm("N", "N", 4, 5, 6, 6, max_ld + 1, 5) == E_UNSUP
+    p = C.c_void_p(0x1000)
+    assert L.ulsnn_sgemm_planned(0, 1, b"N", b"N", 8, 8, 8, 1.0, p, max_ld + 1, p, 8, 0.0, p, 8, None, 0, None) == E_UNSUP
+    assert _grad(_desc(n_out=max_ld + 1)) == E_UNSUP
+    assert _grad(_desc(n_in=max_ld + 8)) == E_UNSUP
+
+
+def test_check_labels_argument_errors():
+    L = ulsnn.load()
+    p = C.c_void_p(0x1000)
+    assert L.ulsnn_check_labels(p, -1, 10, p, None) == E_DIM
+    assert L.ulsnn_check_labels(p, 5, 0, p, None) == E_DIM
+    assert L.ulsnn_check_labels(None, 5, 10, p, None) == E_NULL
+    assert L.ulsnn_check_labels(p, 5, 10, None, None) == E_NULL
+
+
+def test_plan_description_lists_the_shorter_last_pass():
+    text = ulsnn.mlp_grad_describe_plan(400, 480, 3203, 87104)        # 65536 + 21568
+    lines = text.strip().splitlines()
+    assert lines[0].startswith("rows_per_pass=65536") and len(lines) == 12
+    assert lines[6].startswith("tail_rows=21568")
+    assert [l.split(":")[0] for l in lines[7:]] == ["hidden_layer", "output_layer", "dW2", "hidden_delta", "dW1"]
+    # a whole number of passes has no tail section, and its first pass is planned like any 65536-row pass
+    whole = ulsnn.mlp_grad_describe_plan(400, 480, 3203, 262144).strip().splitlines()
+    assert len(whole) == 6 and whole[1:] == lines[1:6]
+
+
+class _NoLaunch:
+    """Stands in for the loaded library: any call through it fails the test."""
+
+    def __getattr__(self, name):
+        raise AssertionError(f"the binding called {name} although an argument was invalid")
+
+
+def test_binding_checks_every_tensor_before_calling_the_library(monkeypatch):
+    """Wrong dtype, shape, size or layout of ANY tensor argument (biases and caller-supplied outputs included)
+    raises in Python; the library, which would hand the pointers to kernels, is never reached.  The device
+    predicate is replaced so that the checks can run on CPU tensors here."""
+    import torch
+    from paper_1911_05181_amd import binding as b
+
+    real_lib = b.load()
+    monkeypatch.setattr(b, "_on_gpu", lambda t: isinstance(t, torch.Tensor))
+    monkeypatch.setattr(b, "load", lambda: _NoLaunch())
+    monkeypatch.setattr(b, "mlp_grad_workspace_bytes", lambda *a: 1024)
+    n_in, n_hid, n_out, batch = 6, 5, 4, 3
+    W1, W2 = torch.zeros(n_in, n_hid), torch.zeros(n_hid, n_out)
+    X, y = torch.zeros(batch, n_in), torch.zeros(batch, dtype=torch.int32)
+    b1, b2 = torch.zeros(n_hid), torch.zeros(n_out)
+
+    def out(**kw):
+        o = b.MlpGradResult(torch.zeros(n_in, n_hid), torch.zeros(n_hid, n_out), torch.zeros(1), torch.zeros(n_hid),
+                            torch.zeros(n_out))
+        for k, v in kw.items():
+            setattr(o, k, v)
+        return o
+
+    bad = [
+        dict(b1=b1.double(), b2=b2), dict(b1=b1, b2=b2[:3]), dict(b1=torch.zeros(n_hid + 1), b2=b2),
+        dict(b1=b1, b2=torch.zeros(2 * n_out)[::2]),
+        dict(out=out(dW2=torch.zeros(n_hid, n_out + 1))), dict(out=out(dW1=torch.zeros(n_hid, n_in))),
+        dict(out=out(dW1=torch.zeros(n_in, n_hid, dtype=torch.float64))), dict(out=out(loss=torch.zeros(2))),
+        dict(out=out(dW2=torch.zeros(n_out, n_hid).t())),
+        dict(b1=b1, b2=b2, out=out(db1=torch.zeros(n_hid - 1))), dict(b1=b1, b2=b2, out=out(db2=None)),
+        dict(workspace=[1, 2, 3]),
+    ]
+    for kw in bad:
+        with pytest.raises((TypeError, ValueError)):
+            b.mlp_grad(W1, W2, X, y, **kw)
+    with pytest.raises((TypeError, ValueError)):
+        b.mlp_loss(W1, W2, X, y, loss=torch.zeros(3))
+    # SGEMM: the stored operands must lie inside their tensors
+    A, B, Cm = torch.zeros(4 * 6), torch.zeros(6 * 5), torch.zeros(4 * 5)
+    for args in [("N", "N", 4, 5, 6, 1.0, A, 7, B, 5, 0.0, Cm, 5),      # lda 7: A would need 27 elements
+                 ("N", "N", 4, 5, 6, 1.0, A, 6, B, 6, 0.0, Cm, 5),      # ldb 6: B would need 35
+                 ("N", "N", 4, 5, 6, 1.0, A, 6, B, 5, 0.0, Cm, 6),      # ldc 6: C would need 23
+                 ("T", "N", 5, 5, 6, 1.0, A, 5, B, 5, 0.0, torch.zeros(25), 5),   # A stored 6 x 5 with lda 5: 30 > 24
+                 ("N", "T", 4, 6, 6, 1.0, A, 6, B, 6, 0.0, torch.zeros(24), 6)]:  # B stored 6 x 6: 36 > 30
+        with pytest.raises(ValueError):
+            b.sgemm(*args)
+        with pytest.raises(ValueError):
+            b.sgemm_planned(5, 1, *args)
+    del real_lib
