@@ -13,8 +13,11 @@ square sizes of the second workload (reported under "sgemm").
 
 "roofline" describes the dominant kernel of the step: the matrix-core GEMM launch that takes the most time,
 timed live with HIP events recorded on the launch stream (ulsnn_mlp_grad_timed), against the MI355X fp32 matrix
-peak of 157.3 TFLOP/s.  "cpu_baseline" is the CPU oracle (float arithmetic) timed on the host cores on the same
-workload.
+peak of 157.3 TFLOP/s (nominal 2.4 GHz) and, as "frac_at_measured_clock", against the same 256 flop per clock and
+compute unit at the shader clock a probe wavefront measured while the step was running ("device").
+"unsettled" is the same K steps timed straight after the W warm-up steps of a fresh process, before any settling.
+"cpu_baseline" is the CPU oracle (float arithmetic) timed on the host cores on the same workload;
+"cpu_baselines" holds it for the other workloads (small network, SGEMM, bf16-rounded inputs), on stated samples.
 """
 from __future__ import annotations
 
@@ -29,10 +32,22 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3      # 256 CUs x 256 flop/clk/CU x 2.4 GHz
-# HBM bytes per launch of the dominant kernel (paired backward products, batch 4096): rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE, each scaled by what the same counter reads for a 1 GiB copy (2.000 and 1.000); 189.5 MB read,
-# 55.4 MB written.  Source: profiles/mlp_grad_b4096_hbm_traffic_pmc.md.  Algorithmic: 119.0 MB read, 54.3 MB written.
-PMC_TRAFFIC_BYTES = {"backward_products": 244.9e6}
+FLOP_PER_CLK_PER_CU = 256          # fp32 matrix instructions
+# HBM bytes per launch of each stage's kernels (calibrated rocprofv3 counters) are read from this summary at run time:
+# its lines "bench_traffic: stage=<name> bytes_per_launch=<n>".
+TRAFFIC_PROFILE = os.path.join("profiles", "mlp_grad_b4096_hbm_traffic_pmc.md")
+
+
+def pmc_traffic():
+    out = {}
+    try:
+        for line in open(os.path.join(ROOT, TRAFFIC_PROFILE)):
+            if line.startswith("bench_traffic:"):
+                f = dict(kv.split("=") for kv in line.split()[1:])
+                out[f["stage"]] = float(f["bytes_per_launch"])
+    except OSError:
+        pass
+    return out
 METRIC = "fp32 GFLOP/s (% of MFMA FP32 peak); MLP gradient patterns/sec"
 BATCH = 4096
 SEED = 2
@@ -54,8 +69,9 @@ def parse():
     ap.add_argument("--no-small-net", action="store_true", help="skip the 64-32-10 latency measurement")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip the squared-error, error-only and optimiser-step measurements (batch 4096)")
-    ap.add_argument("--epoch", action="store_true",
-                    help="also time the whole 9,000,000-pattern epoch (14.4 GB of patterns generated on the GPU)")
+    ap.add_argument("--no-epoch", action="store_true",
+                    help="skip the whole 9,000,000-pattern epoch (14.4 GB of patterns generated on the GPU)")
+    ap.add_argument("--epoch", action="store_true", help="accepted for compatibility: the epoch runs by default")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (reference for HBM byte counters)")
     return ap.parse_args()
@@ -107,6 +123,59 @@ def bench_sgemm(ulsnn, si, torch, sizes):
     return out
 
 
+def bench_sgemm_strided_and_cold(ulsnn, si, torch, sizes):
+    """The paper times its SGEMM with a stride that differs from the row length and with the caches flushed
+    (section 3.4).  "ld_plus_8" / "ld_odd": all three operands stored with leading dimension N + 8 / N + 1 (rows
+    then start 32 / 4 bytes off the 16-byte grid), throughput timing as in bench_sgemm.  "cold": sizes up to 1024,
+    one call at a time, a 512 MB buffer rewritten between calls so that no operand is left in L2 or the Infinity
+    Cache; median of the calls."""
+    out = {}
+    big = max((s_ for s_ in sizes if s_ >= 2048), default=None)
+    if big is not None:
+        m = n = k = big
+        for tag, pad in (("ld_plus_8", 8), ("ld_odd", 1)):
+            ld = big + pad
+            A, B, C0 = si.gemm_operands(1, m, k, k, n, m, n, ld, ld, ld, device="cuda:0")
+            for ta, tb in (("N", "N"), ("N", "T"), ("T", "N")):
+                Cm = C0.clone()
+                settle(torch, lambda: ulsnn.sgemm(ta, tb, m, n, k, 1.0, A, ld, B, ld, 0.5, Cm, ld), 0.03)
+                reps = 10
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    ulsnn.sgemm(ta, tb, m, n, k, 1.0, A, ld, B, ld, 0.5, Cm, ld)
+                e1.record()
+                e1.synchronize()
+                per_call = e0.elapsed_time(e1) / reps
+                gf = ulsnn.sgemm_flops(m, n, k) / (per_call * 1e-3) / 1e9
+                out[f"{ta}{tb}_{big}_{tag}"] = {"ld": ld, "ms": round(per_call, 4), "gflops": round(gf, 1),
+                                               "frac_of_peak": round(gf / (PEAK_FP32_MFMA_TFLOPS * 1e3), 4)}
+            del A, B, C0
+    scrub = torch.empty(128 << 20, dtype=torch.float32, device="cuda:0")      # 512 MB > 256 MB Infinity Cache
+    for size in (s_ for s_ in sizes if s_ <= 1024):
+        m = n = k = size
+        A, B, C0 = si.gemm_operands(1, m, k, k, n, m, n, device="cuda:0")
+        for ta, tb in (("N", "N"), ("N", "T"), ("T", "N")):
+            Cm = C0.clone()
+            times = []
+            for _ in range(9):
+                scrub.fill_(1.0)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                ulsnn.sgemm(ta, tb, m, n, k, 1.0, A, k, B, n, 0.5, Cm, n)
+                e1.record()
+                e1.synchronize()
+                times.append(e0.elapsed_time(e1))
+            times.sort()
+            ms = times[len(times) // 2]
+            gf = ulsnn.sgemm_flops(m, n, k) / (ms * 1e-3) / 1e9
+            out[f"{ta}{tb}_{size}_cold"] = {"ms_single": round(ms, 4), "gflops": round(gf, 1),
+                                            "frac_of_peak": round(gf / (PEAK_FP32_MFMA_TFLOPS * 1e3), 4)}
+        del A, B, C0
+    del scrub
+    return out
+
+
 def cpu_baseline(si, shape, W1, W2, X, y):
     import numpy as np
 
@@ -118,6 +187,49 @@ def cpu_baseline(si, shape, W1, W2, X, y):
     return {"value": round(flops / dt / 1e9, 3), "unit": "GFLOP/s", "cores": oracle.threads(), "kind": "oracle",
             "sample": f"the whole workload once: {X.shape[0]} patterns, float-arithmetic oracle, {dt:.2f} s",
             "patterns_per_s": round(X.shape[0] / dt, 1), "loss": g.loss}
+
+
+def cpu_baselines_other(si, torch, shape, W1, W2):
+    """The oracle timed on the other workloads, each on a bounded, stated sample (a few seconds of host time)."""
+    import numpy as np
+
+    import oracle
+    out = {}
+    # small network, batch 256, with biases: the whole workload, repeated
+    sm = si.MLP_SMALL
+    sW1, sW2, sb1, sb2 = (t.numpy() for t in si.mlp_weights(sm, 0))
+    sX, sy = (t.numpy() for t in si.mlp_patterns(sm, 0, 0, 256))
+    reps = 20
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        oracle.mlp_grad(sW1, sW2, sX, sy, sb1, sb2, dtype=np.float32)
+    dt = (time.perf_counter() - t0) / reps
+    out["small_net"] = {"value": round(oracle.grad_flops(256, sm.n_in, sm.n_hid, sm.n_out) / dt / 1e9, 3),
+                        "unit": "GFLOP/s", "us_per_call": round(dt * 1e6, 1), "cores": oracle.threads(), "kind": "oracle",
+                        "sample": f"64-32-10, batch 256, with biases: the whole workload, mean of {reps} calls"}
+    # SGEMM, the naive three-loop product (float accumulator): whole products up to 1024, a row slice at 4096
+    for size, rows in ((256, 256), (1024, 1024), (4096, 128)):
+        A, B, C0 = si.gemm_operands(1, size, size, size, size, size, size)
+        A, B, C0 = A.numpy(), B.numpy(), C0.numpy()
+        for ta, tb in (("N", "N"), ("N", "T"), ("T", "N")) if size <= 1024 else (("N", "N"),):
+            t0 = time.perf_counter()
+            oracle.sgemm(ta, tb, rows, size, size, 1.0, A, size, B, size, 0.5, C0, size)
+            dt = time.perf_counter() - t0
+            what = "whole product" if rows == size else f"first {rows} rows of C (1/{size // rows} of the product)"
+            out[f"sgemm_{ta}{tb}_{size}"] = {"value": round(oracle.sgemm_flops(rows, size, size) / dt / 1e9, 3),
+                                            "unit": "GFLOP/s", "seconds": round(dt, 4), "cores": oracle.threads(),
+                                            "kind": "oracle", "sample": f"M=N=K={size}, alpha 1, beta 0.5: {what}"}
+    # bf16 workload: the float oracle on the inputs rounded to bf16, first 4096 of the 65536 patterns
+    rb = lambda t: t.to(torch.bfloat16).float().numpy()
+    Xs, ys = si.mlp_patterns(shape, SEED, 0, 4096)
+    t0 = time.perf_counter()
+    oracle.mlp_grad(rb(W1), rb(W2), rb(Xs), ys.numpy(), dtype=np.float32)
+    dt = time.perf_counter() - t0
+    out["bf16_inputs"] = {"value": round(oracle.grad_flops(4096, shape.n_in, shape.n_hid, shape.n_out) / dt / 1e9, 3),
+                          "unit": "GFLOP/s", "seconds": round(dt, 3), "cores": oracle.threads(), "kind": "oracle",
+                          "sample": "400-480-3203 on inputs rounded to bf16: the first 4096 of the 65536 patterns "
+                                    "(1/16 of the workload), float arithmetic"}
+    return out
 
 
 def bench_variants(ulsnn, si, torch, shape, W1, W2, X, y, ws):
@@ -213,6 +325,17 @@ def main():
     out = ulsnn.MlpGradResult(torch.empty_like(W1), torch.empty_like(W2), torch.empty(1, device=dev))
     flops = ulsnn.mlp_grad_flops(shape.n_in, shape.n_hid, shape.n_out, BATCH)
 
+    # what a fresh process gives straight after the W warm-up steps: its first tens of milliseconds under load run
+    # at a lower clock
+    for _ in range(args.warmup):
+        ulsnn.mlp_grad(W1, W2, X, y, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ulsnn.mlp_grad(W1, W2, X, y, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    dt_cold = time.perf_counter() - t0
+
     # untimed: bring clocks and queues to their steady state, then the W warm-up steps
     settle_steps = 0
     t_settle = time.perf_counter()
@@ -233,6 +356,25 @@ def main():
     gflops = flops * args.steps / dt / 1e9
     loss = out.loss.item()
 
+    # shader clock while the step runs: a probe wavefront on a second stream reads the cycle counter and the wall
+    # clock for 20 ms in the middle of a run of the same steps
+    info = ulsnn.device_info()
+    probe_out = torch.zeros(2, dtype=torch.int64, device=dev)
+    side = torch.cuda.Stream()
+    n_probe = max(60, int(0.045 / (ms_per_step * 1e-3)))
+    for i in range(n_probe):
+        if i == 10:
+            ulsnn.clock_probe(20.0, probe_out, stream=side)
+        ulsnn.mlp_grad(W1, W2, X, y, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    cycles, ticks = (int(v) for v in probe_out.tolist())
+    sclk_mhz = cycles / ticks * info["wall_clock_khz"] / 1e3 if ticks > 0 else None
+    peak_at_clock = info["compute_units"] * FLOP_PER_CLK_PER_CU * sclk_mhz * 1e6 / 1e12 if sclk_mhz else None
+    device = {"compute_units": info["compute_units"], "max_shader_clock_mhz": info["max_shader_clock_khz"] / 1e3,
+              "shader_clock_mhz_under_load": round(sclk_mhz, 1) if sclk_mhz else None,
+              "probe_window_ms": round(ticks / info["wall_clock_khz"], 3) if ticks > 0 else None,
+              "fp32_mfma_peak_at_measured_clock_tflops": round(peak_at_clock, 2) if peak_at_clock else None}
+
     # per-stage durations from HIP events on the launch stream (same kernels, same workspace)
     reps = max(5, min(args.steps, 20))
     acc = {k: 0.0 for k in ulsnn.MLP_STAGES}
@@ -249,7 +391,9 @@ def main():
     achieved = stage_flops[dom] / (acc[dom] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": f"fp32 MFMA GEMM launch of stage '{dom}'", "achieved": round(achieved, 2),
                 "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4),
-                "traffic": PMC_TRAFFIC_BYTES.get(dom), "traffic_unit": "bytes of HBM per launch (calibrated PMC)",
+                "frac_at_measured_clock": round(achieved / peak_at_clock, 4) if peak_at_clock else None,
+                "traffic": pmc_traffic().get(dom), "traffic_unit": "bytes of HBM per launch (calibrated PMC)",
+                "traffic_source": TRAFFIC_PROFILE,
                 "flops_per_launch": stage_flops[dom], "avg_launch_ms": round(acc[dom], 4)}
 
     result = {
@@ -261,6 +405,12 @@ def main():
                    "batch": BATCH, "flops_per_step": flops},
         "patterns_per_s": round(BATCH * args.steps / dt, 1),
         "frac_of_fp32_mfma_peak": round(gflops / (PEAK_FP32_MFMA_TFLOPS * 1e3), 4),
+        "frac_at_measured_clock": round(gflops / 1e3 / peak_at_clock, 4) if peak_at_clock else None,
+        "unsettled": {"ms_per_step": round(dt_cold / args.steps * 1e3, 4),
+                      "gflops": round(flops * args.steps / dt_cold / 1e9, 1),
+                      "frac_of_fp32_mfma_peak": round(flops * args.steps / dt_cold / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4),
+                      "note": "the same K steps timed straight after the W warm-up steps of the fresh process"},
+        "device": device,
         "loss": loss, "stages": stages, "roofline": roofline,
     }
     def time_batch(W1_, W2_, X_, y_, reps):
@@ -307,7 +457,7 @@ def main():
                                "gflops": round(ulsnn.mlp_grad_flops(sm.n_in, sm.n_hid, sm.n_out, 256) / sec / 1e9, 2)}
     if not args.no_variants:
         result["variants"] = bench_variants(ulsnn, si, torch, shape, W1, W2, X, y, ws)
-    if args.epoch:
+    if not args.no_epoch:
         # the epoch workload (BASELINE configs[3]): 9,000,000 patterns resident in HBM, chunks of 262144 summed
         n_ep, chunk = 9_000_000, 262144
         Xe = torch.empty(n_ep, shape.n_in, device=dev)
@@ -349,8 +499,10 @@ def main():
         del src, dst
     if not args.no_sgemm:
         result["sgemm"] = bench_sgemm(ulsnn, si, torch, args.sgemm_sizes)
+        result["sgemm"].update(bench_sgemm_strided_and_cold(ulsnn, si, torch, args.sgemm_sizes))
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(si, shape, W1c, W2c, Xc, yc)
+        result["cpu_baselines"] = cpu_baselines_other(si, torch, shape, W1c, W2c)
     else:
         result["cpu_baseline"] = None
     print(json.dumps(result), flush=True)

@@ -279,6 +279,18 @@ int ulsnn_sgemm_planned(int tile_shape, int k_splits, char transa, char transb, 
  */
 int ulsnn_sgemm_describe_plan(char transa, char transb, int m, int n, int k, char *buf, size_t buf_bytes);
 
+/*
+ * Measurement aids (what a roofline fraction "at the measured clock" needs; the paper times wall clock, section 3.4).
+ * ulsnn_device_info: compute units, maximum shader clock and rate of the constant wall clock of the current device
+ * (kHz); any pointer may be NULL.  ULSNN_ERR_HIP without a device.
+ * ulsnn_clock_probe: queues ONE wavefront on hip_stream that reads the shader cycle counter and the wall clock for
+ * about window_ms milliseconds (0 < window_ms <= 1000; it ends by itself after a bounded number of readings) and
+ * writes cycles_and_ticks[0] = shader cycles, [1] = wall-clock ticks elapsed (device memory, two 64-bit values).
+ * Queued on a second stream beside a workload, cycles / ticks * wall clock rate is the shader clock under that load.
+ */
+int ulsnn_device_info(int *compute_units, int *max_shader_clock_khz, int *wall_clock_khz);
+int ulsnn_clock_probe(double window_ms, unsigned long long *cycles_and_ticks, void *hip_stream);
+
 /* Counting conventions (host-only): 2mnk (section 3.1) and batch*(4 n_in n_hid + 6 n_hid n_out) (section 6.2). */
 double ulsnn_sgemm_flops(int m, int n, int k);
 double ulsnn_mlp_grad_flops(int n_in, int n_hid, int n_out, int64_t batch);

@@ -30,6 +30,8 @@ from .binding import (  # noqa: F401
     MLP_STAGES,
     mlp_grad_workspace_bytes,
     check_labels,
+    device_info,
+    clock_probe,
     sgemm,
     sgemm_flops,
     status_string,

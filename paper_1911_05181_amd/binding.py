@@ -92,6 +92,10 @@ def load():
     L.ulsnn_sgemm_describe_plan.restype = i
     L.ulsnn_mlp_grad_describe_plan.argtypes = [C.POINTER(_MlpDesc), i, C.c_char_p, C.c_size_t]
     L.ulsnn_mlp_grad_describe_plan.restype = i
+    L.ulsnn_device_info.argtypes = [C.POINTER(i), C.POINTER(i), C.POINTER(i)]
+    L.ulsnn_device_info.restype = i
+    L.ulsnn_clock_probe.argtypes = [C.c_double, vp, vp]
+    L.ulsnn_clock_probe.restype = i
     L.ulsnn_sgemm_flops.argtypes = [i, i, i]
     L.ulsnn_sgemm_flops.restype = C.c_double
     L.ulsnn_mlp_grad_flops.argtypes = [i, i, i, C.c_int64]
@@ -110,6 +114,24 @@ def status_string(status: int) -> str:
 
 def version() -> int:
     return int(load().ulsnn_version())
+
+
+def device_info() -> dict:
+    """Compute units, maximum shader clock and wall-clock rate (kHz) of the current device (ulsnn_device_info)."""
+    cu, sclk, wall = C.c_int(0), C.c_int(0), C.c_int(0)
+    rc = load().ulsnn_device_info(C.byref(cu), C.byref(sclk), C.byref(wall))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_device_info")
+    return {"compute_units": cu.value, "max_shader_clock_khz": sclk.value, "wall_clock_khz": wall.value}
+
+
+def clock_probe(window_ms: float, out: torch.Tensor, stream=None) -> None:
+    """Queue the clock probe (ulsnn_clock_probe); `out` is a two-element int64 GPU tensor: shader cycles, wall ticks."""
+    if not (_on_gpu(out) and out.dtype == torch.int64 and out.numel() == 2 and out.is_contiguous()):
+        raise TypeError("out must be a contiguous two-element int64 tensor on the GPU")
+    rc = load().ulsnn_clock_probe(float(window_ms), _ptr(out), _stream(stream))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_clock_probe")
 
 
 def sgemm_flops(m: int, n: int, k: int) -> float:

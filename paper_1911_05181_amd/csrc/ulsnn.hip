@@ -1351,6 +1351,38 @@ int ulsnn_sgemm_planned(int tile_shape, int k_splits, char transa, char transb, 
     return launch_reduce(p.splits, EPI_AXPBY, a, (const float *)workspace, s) == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
 }
 
+int ulsnn_device_info(int *compute_units, int *max_shader_clock_khz, int *wall_clock_khz)
+{
+    int dev = 0, cu = 0, sclk = 0, wall = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipDeviceGetAttribute(&sclk, hipDeviceAttributeClockRate, dev) != hipSuccess ||
+        hipDeviceGetAttribute(&wall, hipDeviceAttributeWallClockRate, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return ULSNN_ERR_HIP;
+    }
+    if (compute_units) *compute_units = cu;
+    if (max_shader_clock_khz) *max_shader_clock_khz = sclk;
+    if (wall_clock_khz) *wall_clock_khz = wall;
+    return ULSNN_OK;
+}
+
+int ulsnn_clock_probe(double window_ms, unsigned long long *cycles_and_ticks, void *hip_stream)
+{
+    if (!cycles_and_ticks) return ULSNN_ERR_NULL;
+    if (!(window_ms > 0.0) || window_ms > 1000.0) return ULSNN_ERR_DIM;
+    int wall_khz = 0;
+    const int rc = ulsnn_device_info(nullptr, nullptr, &wall_khz);
+    if (rc != ULSNN_OK) return rc;
+    if (wall_khz <= 0) return ULSNN_ERR_UNSUPPORTED;
+    const unsigned long long ticks = (unsigned long long)(window_ms * (double)wall_khz);
+    // one reading takes well over 100 ns (the sleep alone is 32 x 64 cycles): the cap only guards the exit
+    const unsigned int max_iterations = (unsigned int)std::min(1.0e8, window_ms * 2.0e4 + 1000.0);
+    hipLaunchKernelGGL(clock_probe_kernel, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, ticks, max_iterations,
+                       cycles_and_ticks);
+    return hipGetLastError() == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
+}
+
 double ulsnn_sgemm_flops(int m, int n, int k) { return 2.0 * (double)m * (double)n * (double)k; }
 
 double ulsnn_mlp_loss_flops(int n_in, int n_hid, int n_out, int64_t batch)

@@ -79,4 +79,25 @@ __global__ __launch_bounds__(256) void add_scaled_kernel(size_t n, const float *
         out[i] = w[i] + alpha * x[i];
 }
 
+// Measurement aid: one wavefront reads the shader cycle counter and the constant-rate wall clock until
+// `wall_ticks` ticks of the latter have passed (or `max_iterations` readings, so that it always ends), and writes
+// out[0] = shader cycles, out[1] = wall-clock ticks that elapsed in between.  Launched beside a workload, the
+// quotient is the shader clock the chip ran at under that workload.
+__global__ __launch_bounds__(64) void clock_probe_kernel(unsigned long long wall_ticks, unsigned int max_iterations,
+                                                         unsigned long long *__restrict__ out)
+{
+    const unsigned long long t0 = wall_clock64();
+    const unsigned long long c0 = clock64();
+    unsigned long long t1 = t0, c1 = c0;
+    for (unsigned int it = 0; it < max_iterations && t1 - t0 < wall_ticks; ++it) {
+        __builtin_amdgcn_s_sleep(32);
+        c1 = clock64();
+        t1 = wall_clock64();
+    }
+    if (threadIdx.x == 0) {
+        out[0] = c1 - c0;
+        out[1] = t1 - t0;
+    }
+}
+
 }  // namespace ulsnn
