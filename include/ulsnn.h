@@ -127,6 +127,23 @@ int ulsnn_mlp_grad(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, c
                    const int32_t *labels, int batch, float *dW1, float *dW2, float *loss);
 
 /*
+ * ulsnn_mlp_grad for callers that cannot allocate device memory or carry a workspace around: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The same operation, kernels, results and error
+ * rules as ulsnn_mlp_grad, but the scratch is a static device array inside the library of
+ * ULSNN_STATIC_SCRATCH_BYTES bytes (held on every GPU the library runs on until the process ends); desc->workspace
+ * and desc->workspace_bytes are ignored.  A network / batch whose ulsnn_mlp_grad_workspace_bytes exceeds that size
+ * returns ULSNN_ERR_WORKSPACE and queues nothing.  The call allocates and frees nothing.  The array's address on the
+ * current device is looked up on the first call on that device (or by ulsnn_static_scratch_init, which callers
+ * that capture the call in a graph should run once, outside the capture, with the device current).  All calls on
+ * one GPU share the one array: calls that may overlap on a GPU (different streams or host threads) race; order them.
+ */
+#define ULSNN_STATIC_SCRATCH_BYTES (64u << 20)
+size_t ulsnn_static_scratch_bytes(void);
+int ulsnn_static_scratch_init(void);
+int ulsnn_mlp_grad_static(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X,
+                          const int32_t *labels, int batch, float *dW1, float *dW2, float *loss);
+
+/*
  * Debug helper for the label rule above: *count (ONE device int64) = number of labels[0..batch) outside
  * [0, n_out), i.e. of patterns ulsnn_mlp_grad would ignore.  Asynchronous on hip_stream.  batch == 0 gives 0.
  */

@@ -60,6 +60,12 @@ def load():
     L.ulsnn_mlp_grad_workspace_bytes.restype = C.c_size_t
     L.ulsnn_mlp_grad.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, i, vp, vp, vp]
     L.ulsnn_mlp_grad.restype = i
+    L.ulsnn_mlp_grad_static.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, i, vp, vp, vp]
+    L.ulsnn_mlp_grad_static.restype = i
+    L.ulsnn_static_scratch_bytes.argtypes = []
+    L.ulsnn_static_scratch_bytes.restype = C.c_size_t
+    L.ulsnn_static_scratch_init.argtypes = []
+    L.ulsnn_static_scratch_init.restype = i
     L.ulsnn_check_labels.argtypes = [vp, C.c_int64, i, vp, vp]
     L.ulsnn_check_labels.restype = i
     L.ulsnn_mlp_grad_epoch.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, C.c_int64, i, vp, vp, vp]
@@ -432,6 +438,28 @@ def mlp_grad(W1, W2, X, labels, b1=None, b2=None, *, out: Optional[MlpGradResult
     if rc:
         raise UlsnnError(rc, "ulsnn_mlp_grad")
     return out
+
+
+def mlp_grad_static(W1, W2, X, labels, b1=None, b2=None, *, out: Optional[MlpGradResult] = None, accumulate=False,
+                    stream=None) -> MlpGradResult:
+    """ulsnn_mlp_grad_static: the gradient with the library's built-in scratch array instead of a workspace."""
+    n_in, n_hid, n_out, out, odt = _mlp_common(W1, W2, X, labels, b1, b2, out, accumulate)
+    d = _desc(n_in, n_hid, n_out, b1, b2, out.db1, out.db2, accumulate, None, stream, odt)
+    rc = load().ulsnn_mlp_grad_static(C.byref(d), _ptr(W1), _ptr(W2), _ptr(X), _ptr(labels), X.shape[0],
+                                      _ptr(out.dW1), _ptr(out.dW2), _ptr(out.loss))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_mlp_grad_static")
+    return out
+
+
+def static_scratch_bytes() -> int:
+    return int(load().ulsnn_static_scratch_bytes())
+
+
+def static_scratch_init() -> None:
+    rc = load().ulsnn_static_scratch_init()
+    if rc:
+        raise UlsnnError(rc, "ulsnn_static_scratch_init")
 
 
 def check_labels(labels: torch.Tensor, n_out: int, *, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:

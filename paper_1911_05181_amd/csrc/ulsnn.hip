@@ -8,6 +8,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdio>
+#include <mutex>
 
 #include "gemm.hpp"
 #include "gemm_bf16.hpp"
@@ -16,6 +17,10 @@
 #include "vec_kernels.hpp"
 
 using namespace ulsnn;
+
+// Built-in scratch of ulsnn_mlp_grad_static (callers that cannot allocate a workspace).  In host code this name is
+// only a handle for hipGetSymbolAddress: the device address, one per GPU, is resolved by static_scratch() below.
+static __device__ __align__(256) unsigned char scratch[ULSNN_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -972,6 +977,45 @@ int ulsnn_mlp_grad(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, c
     if (rc != ULSNN_OK) return rc;
     return mlp_grad_impl(desc, W1, W2, X, MlpTask{labels, nullptr, true}, batch, dW1, dW2, loss,
                          desc->accumulate != 0);
+}
+
+// Device address of `scratch` on the current device, resolved once per device.
+static int static_scratch(void **out)
+{
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static void *address[MAX_DEVICES] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return ULSNN_ERR_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!address[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ULSNN_ERR_HIP;
+        address[dev] = p;
+    }
+    *out = address[dev];
+    return ULSNN_OK;
+}
+
+size_t ulsnn_static_scratch_bytes(void) { return (size_t)ULSNN_STATIC_SCRATCH_BYTES; }
+
+int ulsnn_static_scratch_init(void)
+{
+    void *p = nullptr;
+    return static_scratch(&p);
+}
+
+int ulsnn_mlp_grad_static(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X,
+                          const int32_t *labels, int batch, float *dW1, float *dW2, float *loss)
+{
+    const int rc = check_mlp_args(desc, W1, W2, X, labels, batch, dW1, dW2, loss, true);
+    if (rc != ULSNN_OK) return rc;
+    if (batch > 0 && mlp_layout(desc, batch).bytes > (size_t)ULSNN_STATIC_SCRATCH_BYTES) return ULSNN_ERR_WORKSPACE;
+    ulsnn_mlp_desc d = *desc;
+    const int rs = static_scratch(&d.workspace);
+    if (rs != ULSNN_OK) return rs;
+    d.workspace_bytes = (size_t)ULSNN_STATIC_SCRATCH_BYTES;
+    return mlp_grad_impl(&d, W1, W2, X, MlpTask{labels, nullptr, true}, batch, dW1, dW2, loss, d.accumulate != 0);
 }
 
 int ulsnn_check_labels(const int32_t *labels, int64_t batch, int n_out, int64_t *count, void *hip_stream)

@@ -257,13 +257,19 @@ def test_leading_dimension_and_network_size_limits():
     assert _grad(_desc(n_in=max_ld + 8)) == E_UNSUP
 
 
-def test_check_labels_argument_errors():
+def test_check_labels_and_static_scratch_argument_errors():
     L = ulsnn.load()
     p = C.c_void_p(0x1000)
     assert L.ulsnn_check_labels(p, -1, 10, p, None) == E_DIM
     assert L.ulsnn_check_labels(p, 5, 0, p, None) == E_DIM
     assert L.ulsnn_check_labels(None, 5, 10, p, None) == E_NULL
     assert L.ulsnn_check_labels(p, 5, 10, None, None) == E_NULL
+    assert ulsnn.static_scratch_bytes() == 64 << 20
+    # validation comes first, then the size check against the built-in array: neither touches the GPU
+    assert L.ulsnn_mlp_grad_static(None, p, p, p, p, 8, p, p, p) == E_NULL
+    assert L.ulsnn_mlp_grad_static(C.byref(_desc()), p, p, None, p, 8, p, p, p) == E_NULL
+    assert ulsnn.mlp_grad_workspace_bytes(400, 480, 3203, 4096) > ulsnn.static_scratch_bytes()
+    assert L.ulsnn_mlp_grad_static(C.byref(_desc()), p, p, p, p, 4096, p, p, p) == E_WS
 
 
 def test_plan_description_lists_the_shorter_last_pass():
@@ -321,6 +327,8 @@ def test_binding_checks_every_tensor_before_calling_the_library(monkeypatch):
             b.mlp_grad(W1, W2, X, y, **kw)
     with pytest.raises((TypeError, ValueError)):
         b.mlp_loss(W1, W2, X, y, loss=torch.zeros(3))
+    with pytest.raises((TypeError, ValueError)):
+        b.mlp_grad_static(W1, W2, X, y, b1, b2, out=out(db1=torch.zeros(1)))
     # SGEMM: the stored operands must lie inside their tensors
     A, B, Cm = torch.zeros(4 * 6), torch.zeros(6 * 5), torch.zeros(4 * 5)
     for args in [("N", "N", 4, 5, 6, 1.0, A, 7, B, 5, 0.0, Cm, 5),      # lda 7: A would need 27 elements
