@@ -287,7 +287,8 @@ def bench_variants(ulsnn, si, torch, shape, W1, W2, X, y, ws):
                            "error_evaluations": last.error_evaluations,
                            "gradient_evaluations_on_subset": last.gradient_evaluations, "bracket_batch": bracket,
                            "alpha": last.alpha, "loss_before": last.loss0, "loss_after": last.loss,
-                           "note": "host reads two scalars per evaluation: latency of the evaluations dominates"}
+                           "note": "gradient + direction + line search; the host synchronises once per 8 bracketing "
+                                   "steps and once at the end"}
     # vector primitives: HBM/L2-resident 6.9 MB vectors, launch-latency bound
     dot_out = torch.empty(1, device=dev)
     vws = torch.empty(ulsnn.VEC_WORKSPACE_BYTES, dtype=torch.uint8, device=dev)

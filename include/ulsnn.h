@@ -74,9 +74,11 @@ int ulsnn_sgemm(char transa, char transb, int m, int n, int k, float alpha, cons
  *                    this is how an epoch is summed over chunks of patterns).
  *   operand_dtype: 0 = fp32 storage of W1, W2, X (the paper's precision; section 4.2 reports 32 bits to be enough).
  *                  1 = bf16 storage (section 4.2 notes that 16 bits can suffice for small nets): W1, W2 and X point
- *                      at bf16 values (upper 16 bits of an IEEE float, row-major, dense); H, dO and dA1 are kept in
- *                      bf16 (round to nearest even) and multiplied on the bf16 matrix instructions; every product
- *                      accumulates in fp32; logits, softmax, loss, dW1, dW2, db1, db2 (and b1, b2) stay fp32.
+ *                      at bf16 values (upper 16 bits of an IEEE float, row-major, dense); H, the logits, dO and dA1
+ *                      are kept in bf16 (round to nearest even) and multiplied on the bf16 matrix instructions; every
+ *                      product accumulates in fp32; the softmax statistics (row maximum, sum of exponentials, the
+ *                      label's logit) and with them the loss are taken from the fp32 accumulators of the output
+ *                      layer before its logits are rounded; dW1, dW2, db1, db2 (and b1, b2) stay fp32.
  *                      Fastest when n_in and n_hid are multiples of 8 (16-byte rows); other sizes are correct but
  *                      use an element-wise fetch for the operands whose rows are not 16-byte aligned (W1 and W2
  *                      are re-laid out internally, X is not).  Any other value: ULSNN_ERR_UNSUPPORTED.
@@ -249,8 +251,14 @@ int ulsnn_cg_direction(int64_t n, const float *g_new, const float *g_old, float 
  * does, the last two steps are the bracket.  E is evaluated (all patterns) at lo (E0 if lo = 0), (lo + hi)/2 and
  * hi; if the parabola through these is convex, also at its vertex clamped to the bracket.  The step with the
  * smallest E among those evaluated is applied: W := W + alpha d in place (W unchanged if that step is 0).
- * `result` is HOST memory; the call synchronises hip_stream after every evaluation (it must read the scalars to
- * decide).  desc->workspace must hold ulsnn_mlp_line_search_workspace_bytes(desc, batch) bytes (the gradient
+ * `result` is HOST memory.  The host reads device scalars only where it must decide what to launch next: it
+ * synchronises hip_stream once per group of bracketing steps (groups of 2, 4, 8, 8, ... steps; all steps of a group
+ * are evaluated, also those after
+ * the one that closes the bracket: spare gradients on the small subset instead of a round trip each) and once at the
+ * end; the vertex of the parabola, the comparison of the errors and the weight update use steps computed on the
+ * device (when the parabola is not convex the midpoint is evaluated a second time in the vertex's place).  The
+ * evaluation counts in `result` are the algorithm's own (what a sequential search would have evaluated).
+ * desc->workspace must hold ulsnn_mlp_line_search_workspace_bytes(desc, batch) bytes (the gradient
  * workspace for `batch` patterns plus two weight-sized and two gradient-sized arrays); desc->accumulate is ignored.
  */
 typedef struct {

@@ -30,7 +30,10 @@ enum Epilogue {
     EPI_PARTIAL = 1,    // split-k partial: P[z] = acc (dense, ld = N)
     EPI_BIAS_TANH = 2,  // C = tanh(acc + bias[j])
     EPI_BIAS = 3,       // C = acc + bias[j]
-    EPI_TANHGRAD = 4    // C = acc * (1 - aux[i][j]^2)
+    EPI_TANHGRAD = 4,   // C = acc * (1 - aux[i][j]^2)
+    // bf16-operand kernel only: output layer with the softmax statistics of its rows taken in the epilogue
+    EPI_BIAS_STATS = 5, // C = bf16(acc + bias[j]); per row and column group: max and sum of exp; the label's logit
+    EPI_STATS_ONLY = 6  // the same statistics, C not written (error-only evaluation)
 };
 
 struct GemmArgs {

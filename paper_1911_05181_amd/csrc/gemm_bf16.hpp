@@ -50,6 +50,13 @@ struct Gemm16Args {
     int kchunk;            // k range per split (multiple of 32)
     int tiles_m, tiles_n;
     size_t partial_stride; // EPI_PARTIAL: elements between consecutive partial results
+    // EPI_BIAS_STATS / EPI_STATS_ONLY: softmax statistics of the logits, from the fp32 values before rounding.
+    // stats[i * stat_groups + tile_n * WN + wn] = (max, sum of exp(z - max)) over the columns of row i that the
+    // wavefront column (tile_n, wn) covers; label_logit[i] = z[i][labels[i]] where the label is in range.
+    float2 *stats;
+    int stat_groups;       // tiles_n * WN of the launch's tile shape
+    float *label_logit;
+    const int32_t *labels;
     int aligned;           // 1: A and B rows are 16-byte aligned (fast vector fetch allowed)
     int c_vec;             // 1: rows of C are 16-byte aligned (pointer and ldc): row-wise vector epilogue
     int aux_vec;           // 1: rows of aux are 16-byte aligned
@@ -200,13 +207,255 @@ constexpr int gemm16_lds_elems()
     return 2 * (Panel16<A_KC, Cfg::BM>::SIZE + Panel16<B_KC, Cfg::BN>::SIZE);
 }
 
-// OUT_BF16: C is bf16 (EPI_BIAS_TANH, EPI_TANHGRAD) else fp32.
+// Merge two (max, sum of exp(. - max)) pairs of disjoint column sets; a pair of an empty set is (-inf, 0).
+__device__ __forceinline__ void softmax_merge(float &m, float &s, float om, float os)
+{
+    const float nm = fmaxf(m, om);
+    s = (m == nm ? s : s * __expf(m - nm)) + (om == nm ? os : os * __expf(om - nm));
+    m = nm;
+}
+
+// Epilogue of one tile: the accumulators of this wavefront's sub-tile (rows i0 + wrow.., columns j0 + wcol..) leave
+// through `scratch`, EPILOGUE_SCRATCH_FLOATS floats of LDS private to the wavefront, wherever rows of C are 16-byte
+// aligned.  Every thread of the workgroup must call this (it starts with a workgroup barrier: the operand panels,
+// whose LDS the scratch may reuse, are dead after it).
+constexpr int EPILOGUE_SCRATCH_FLOATS = 32 * 36;
+template <class Cfg, int EPI>
+__device__ __forceinline__ void gemm16_epilogue(const Gemm16Args &g, floatx16 (&acc)[Cfg::TM][Cfg::TN],
+                                                float *scratch, const int i0, const int j0, const int z,
+                                                const int tile_n)
+{
+    constexpr int TM = Cfg::TM, TN = Cfg::TN;
+    constexpr bool OUT_BF16 = (EPI == EPI_BIAS_TANH || EPI == EPI_TANHGRAD || EPI == EPI_BIAS_STATS);
+    constexpr bool STATS = (EPI == EPI_BIAS_STATS || EPI == EPI_STATS_ONLY);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
+    const int wrow = wm * Cfg::WTM, wcol = wn * Cfg::WTN;
+    (void)wm;
+    // Epilogue.  Accumulator register r of a block holds row 8*(r/4) + 4*h + r%4, column lane%32: a lane owns a
+    // COLUMN of the block, so stores straight from the accumulators are one element per lane and instruction
+    // (2 bytes for bf16 results).  With 16-byte aligned rows of C (and of aux) each block instead goes through a
+    // wavefront-private LDS scratch and leaves as rows: every lane handles 8 consecutive columns of one row with
+    // 16-byte loads and stores, an eighth of the memory instructions.
+    float *Cf = (float *)g.C;
+    u16 *Ch = (u16 *)g.C;
+    int ldc = g.ldc;
+    if (EPI == EPI_PARTIAL) {
+        Cf += (size_t)z * g.partial_stride;
+        ldc = g.N;
+    }
+    if constexpr (STATS) {
+        // Output layer with softmax statistics.  Blocks leave through the wavefront-private scratch as rows (as
+        // below): a lane then holds 8 consecutive logits of ONE row, the same row for every block y of its
+        // wavefront's sub-tile, so the row's running (max, sum of exp) stays in registers across y and is joined
+        // over the 4 lanes that share the row with two shuffles.  C (bf16, 16-byte aligned rows: the caller's
+        // workspace) is written unless only the statistics are wanted.
+        constexpr int SLD = 36;
+        __syncthreads();
+        float *scr = scratch;
+        const int srow = lane >> 2, scol = (lane & 3) * 8;
+        const int group = tile_n * Cfg::WN + wn;
+#pragma unroll
+        for (int x = 0; x < TM; ++x) {
+            float rm[2] = {-INFINITY, -INFINITY}, rs[2] = {0.f, 0.f};
+            int lab[2];
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {
+                const int i = i0 + wrow + x * 32 + pass * 16 + srow;
+                lab[pass] = i < g.M ? g.labels[i] : -1;
+            }
+#pragma unroll
+            for (int y = 0; y < TN; ++y) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) scr[(8 * (r / 4) + 4 * h + (r % 4)) * SLD + l32] = acc[x][y][r];
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int pass = 0; pass < 2; ++pass) {
+                    const int row = pass * 16 + srow;
+                    const floatx4 lo = *reinterpret_cast<const floatx4 *>(scr + row * SLD + scol);
+                    const floatx4 hi = *reinterpret_cast<const floatx4 *>(scr + row * SLD + scol + 4);
+                    if (pass == 1) {
+                        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                    }
+                    float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                    const int i = i0 + wrow + x * 32 + row;
+                    const int j = j0 + wcol + y * 32 + scol;
+                    if (i >= g.M || j >= g.N) continue;
+                    float bm = -INFINITY, zl = 0.f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const bool in = j + e < g.N;
+                        v[e] += (g.bias && in) ? g.bias[j + e] : 0.f;
+                        bm = in ? fmaxf(bm, v[e]) : bm;
+                        zl = (lab[pass] == j + e) ? v[e] : zl;
+                    }
+                    const float nm = fmaxf(rm[pass], bm);      // finite: column j itself is inside the matrix
+                    float bs = 0.f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) bs += (j + e < g.N) ? __expf(v[e] - nm) : 0.f;
+                    rs[pass] = (rm[pass] == nm ? rs[pass] : rs[pass] * __expf(rm[pass] - nm)) + bs;
+                    rm[pass] = nm;
+                    if (lab[pass] >= j && lab[pass] < j + 8 && lab[pass] < g.N) g.label_logit[i] = zl;
+                    if (EPI == EPI_BIAS_STATS) {
+                        u16x8 o;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) o[e] = f32_to_bf16(v[e]);
+                        const size_t at = (size_t)i * g.ldc + j;
+                        if (j + 7 < g.N) {
+                            *reinterpret_cast<u16x8 *>(Ch + at) = o;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (j + e < g.N) Ch[at + e] = o[e];
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+                for (int o = 1; o <= 2; o <<= 1) {
+                    const float om = __shfl_xor(rm[pass], o, 64), os = __shfl_xor(rs[pass], o, 64);
+                    softmax_merge(rm[pass], rs[pass], om, os);
+                }
+                const int i = i0 + wrow + x * 32 + pass * 16 + srow;
+                if ((lane & 3) == 0 && i < g.M && j0 + wcol < g.N)
+                    g.stats[(size_t)i * g.stat_groups + group] = make_float2(rm[pass], rs[pass]);
+            }
+        }
+        return;
+    }
+    const bool rows_vec = (EPI == EPI_PARTIAL) ? ((g.N & 3) == 0 && (g.partial_stride & 3) == 0 && g.c_vec) : g.c_vec != 0;
+    if (rows_vec) {
+        constexpr int SLD = 36;                                   // scratch row stride (floats): 16-byte aligned rows
+        __syncthreads();                                          // every wavefront is done reading the panels
+        float *scr = scratch;
+        const int srow = lane >> 2, scol = (lane & 3) * 8;        // this lane's row (of 16 per pass) and 8 columns
+#pragma unroll
+        for (int x = 0; x < TM; ++x) {
+#pragma unroll
+            for (int y = 0; y < TN; ++y) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) scr[(8 * (r / 4) + 4 * h + (r % 4)) * SLD + l32] = acc[x][y][r];
+                // LDS operations of one wavefront complete in order; the fences keep the compiler from moving the
+                // reads of other lanes' elements above these writes (and the next block's writes above the reads)
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int pass = 0; pass < 2; ++pass) {
+                    const int row = pass * 16 + srow;
+                    const floatx4 lo = *reinterpret_cast<const floatx4 *>(scr + row * SLD + scol);
+                    const floatx4 hi = *reinterpret_cast<const floatx4 *>(scr + row * SLD + scol + 4);
+                    if (pass == 1) {
+                        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                        __builtin_amdgcn_wave_barrier();
+                    }
+                    float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                    const int i = i0 + wrow + x * 32 + row;
+                    const int j = j0 + wcol + y * 32 + scol;
+                    if (i >= g.M || j >= g.N) continue;
+                    const bool whole = j + 7 < g.N;
+                    const size_t at = (size_t)i * ldc + j;
+                    if (EPI == EPI_BIAS_TANH || EPI == EPI_BIAS) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] += (g.bias && j + e < g.N) ? g.bias[j + e] : 0.f;
+                    }
+                    if (EPI == EPI_TANHGRAD) {
+                        const u16 *ap = g.aux + (size_t)i * g.ldaux + j;
+                        u16x8 hv;
+                        if (whole && g.aux_vec) {
+                            hv = load8_aligned(ap);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) hv[e] = j + e < g.N ? ap[e] : (u16)0;
+                        }
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const float t = bf16_to_f32(hv[e]);
+                            v[e] *= (1.0f - t * t);
+                        }
+                    }
+                    if (EPI == EPI_BIAS_TANH) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = tanh_f32(v[e]);
+                    }
+                    if (OUT_BF16) {
+                        u16x8 o;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) o[e] = f32_to_bf16(v[e]);
+                        if (whole) {
+                            *reinterpret_cast<u16x8 *>(Ch + at) = o;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (j + e < g.N) Ch[at + e] = o[e];
+                        }
+                    } else {
+                        if (EPI == EPI_AXPBY) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                v[e] *= g.alpha;
+                                if (g.beta != 0.f && j + e < g.N) v[e] += g.beta * Cf[at + e];
+                            }
+                        }
+                        if (whole) {
+                            *reinterpret_cast<floatx4 *>(Cf + at) = floatx4{v[0], v[1], v[2], v[3]};
+                            *reinterpret_cast<floatx4 *>(Cf + at + 4) = floatx4{v[4], v[5], v[6], v[7]};
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (j + e < g.N) Cf[at + e] = v[e];
+                        }
+                    }
+                }
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int y = 0; y < TN; ++y) {
+        const int j = j0 + wcol + y * 32 + l32;
+        if (j >= g.N) continue;
+        float bias = 0.f;
+        if ((EPI == EPI_BIAS_TANH || EPI == EPI_BIAS) && g.bias) bias = g.bias[j];
+#pragma unroll
+        for (int x = 0; x < TM; ++x) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = i0 + wrow + x * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                if (i >= g.M) continue;
+                const float v = acc[x][y][r];
+                const size_t at = (size_t)i * ldc + j;
+                if (EPI == EPI_AXPBY) {
+                    float out = g.alpha * v;
+                    if (g.beta != 0.f) out += g.beta * Cf[at];
+                    Cf[at] = out;
+                } else if (EPI == EPI_PARTIAL) {
+                    Cf[at] = v;
+                } else if (EPI == EPI_BIAS_TANH) {
+                    Ch[at] = f32_to_bf16(tanh_f32(v + bias));
+                } else if (EPI == EPI_BIAS) {
+                    Cf[at] = v + bias;
+                } else {
+                    const float hv = bf16_to_f32(g.aux[(size_t)i * g.ldaux + j]);
+                    Ch[at] = f32_to_bf16(v * (1.0f - hv * hv));
+                }
+            }
+        }
+    }
+    (void)OUT_BF16;
+}
+
+// OUT_BF16: C is bf16 (EPI_BIAS_TANH, EPI_TANHGRAD, EPI_BIAS_STATS) else fp32.
 template <class Cfg, bool A_KC, bool B_KC, int EPI>
 __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, const int splits, u16 *lds)
 {
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = 32, THREADS = Cfg::THREADS;
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
-    constexpr bool OUT_BF16 = (EPI == EPI_BIAS_TANH || EPI == EPI_TANHGRAD);
     using PA = Panel16<A_KC, BM>;
     using PB = Panel16<B_KC, BN>;
     constexpr int NVA = (BM * BK / 8 + THREADS - 1) / THREADS;
@@ -217,7 +466,6 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, h = lane >> 5;
     const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
     const int wrow = wm * Cfg::WTM, wcol = wn * Cfg::WTN;
 
@@ -365,139 +613,9 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
         }
         __syncthreads();
     }
-
-    // Epilogue.  Accumulator register r of a block holds row 8*(r/4) + 4*h + r%4, column lane%32: a lane owns a
-    // COLUMN of the block, so stores straight from the accumulators are one element per lane and instruction
-    // (2 bytes for bf16 results).  With 16-byte aligned rows of C (and of aux) each block instead goes through a
-    // wavefront-private LDS scratch and leaves as rows: every lane handles 8 consecutive columns of one row with
-    // 16-byte loads and stores, an eighth of the memory instructions.
-    float *Cf = (float *)g.C;
-    u16 *Ch = (u16 *)g.C;
-    int ldc = g.ldc;
-    if (EPI == EPI_PARTIAL) {
-        Cf += (size_t)z * g.partial_stride;
-        ldc = g.N;
-    }
-    const bool rows_vec = (EPI == EPI_PARTIAL) ? ((g.N & 3) == 0 && (g.partial_stride & 3) == 0 && g.c_vec) : g.c_vec != 0;
-    if (rows_vec) {
-        constexpr int SLD = 36;                                   // scratch row stride (floats): 16-byte aligned rows
-        static_assert(gemm16_lds_elems<Cfg, A_KC, B_KC>() * 2 >= Cfg::WM * Cfg::WN * 32 * SLD * 4, "scratch fits in the panels' LDS");
-        __syncthreads();                                          // every wavefront is done reading the panels
-        float *scr = reinterpret_cast<float *>(lds) + wave * (32 * SLD);
-        const int srow = lane >> 2, scol = (lane & 3) * 8;        // this lane's row (of 16 per pass) and 8 columns
-#pragma unroll
-        for (int x = 0; x < TM; ++x) {
-#pragma unroll
-            for (int y = 0; y < TN; ++y) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) scr[(8 * (r / 4) + 4 * h + (r % 4)) * SLD + l32] = acc[x][y][r];
-                // LDS operations of one wavefront complete in order; the fences keep the compiler from moving the
-                // reads of other lanes' elements above these writes (and the next block's writes above the reads)
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                for (int pass = 0; pass < 2; ++pass) {
-                    const int row = pass * 16 + srow;
-                    const floatx4 lo = *reinterpret_cast<const floatx4 *>(scr + row * SLD + scol);
-                    const floatx4 hi = *reinterpret_cast<const floatx4 *>(scr + row * SLD + scol + 4);
-                    if (pass == 1) {
-                        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-                    }
-                    float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-                    const int i = i0 + wrow + x * 32 + row;
-                    const int j = j0 + wcol + y * 32 + scol;
-                    if (i >= g.M || j >= g.N) continue;
-                    const bool whole = j + 7 < g.N;
-                    const size_t at = (size_t)i * ldc + j;
-                    if (EPI == EPI_BIAS_TANH || EPI == EPI_BIAS) {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) v[e] += (g.bias && j + e < g.N) ? g.bias[j + e] : 0.f;
-                    }
-                    if (EPI == EPI_TANHGRAD) {
-                        const u16 *ap = g.aux + (size_t)i * g.ldaux + j;
-                        u16x8 hv;
-                        if (whole && g.aux_vec) {
-                            hv = load8_aligned(ap);
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) hv[e] = j + e < g.N ? ap[e] : (u16)0;
-                        }
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            const float t = bf16_to_f32(hv[e]);
-                            v[e] *= (1.0f - t * t);
-                        }
-                    }
-                    if (EPI == EPI_BIAS_TANH) {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) v[e] = tanh_f32(v[e]);
-                    }
-                    if (OUT_BF16) {
-                        u16x8 o;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) o[e] = f32_to_bf16(v[e]);
-                        if (whole) {
-                            *reinterpret_cast<u16x8 *>(Ch + at) = o;
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 8; ++e)
-                                if (j + e < g.N) Ch[at + e] = o[e];
-                        }
-                    } else {
-                        if (EPI == EPI_AXPBY) {
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) {
-                                v[e] *= g.alpha;
-                                if (g.beta != 0.f && j + e < g.N) v[e] += g.beta * Cf[at + e];
-                            }
-                        }
-                        if (whole) {
-                            *reinterpret_cast<floatx4 *>(Cf + at) = floatx4{v[0], v[1], v[2], v[3]};
-                            *reinterpret_cast<floatx4 *>(Cf + at + 4) = floatx4{v[4], v[5], v[6], v[7]};
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 8; ++e)
-                                if (j + e < g.N) Cf[at + e] = v[e];
-                        }
-                    }
-                }
-            }
-        }
-        return;
-    }
-#pragma unroll
-    for (int y = 0; y < TN; ++y) {
-        const int j = j0 + wcol + y * 32 + l32;
-        if (j >= g.N) continue;
-        float bias = 0.f;
-        if ((EPI == EPI_BIAS_TANH || EPI == EPI_BIAS) && g.bias) bias = g.bias[j];
-#pragma unroll
-        for (int x = 0; x < TM; ++x) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int i = i0 + wrow + x * 32 + 8 * (r / 4) + 4 * h + (r % 4);
-                if (i >= g.M) continue;
-                const float v = acc[x][y][r];
-                const size_t at = (size_t)i * ldc + j;
-                if (EPI == EPI_AXPBY) {
-                    float out = g.alpha * v;
-                    if (g.beta != 0.f) out += g.beta * Cf[at];
-                    Cf[at] = out;
-                } else if (EPI == EPI_PARTIAL) {
-                    Cf[at] = v;
-                } else if (EPI == EPI_BIAS_TANH) {
-                    Ch[at] = f32_to_bf16(tanh_f32(v + bias));
-                } else if (EPI == EPI_BIAS) {
-                    Cf[at] = v + bias;
-                } else {
-                    const float hv = bf16_to_f32(g.aux[(size_t)i * g.ldaux + j]);
-                    Ch[at] = f32_to_bf16(v * (1.0f - hv * hv));
-                }
-            }
-        }
-    }
-    (void)OUT_BF16;
+    static_assert(gemm16_lds_elems<Cfg, A_KC, B_KC>() * 2 >= Cfg::WM * Cfg::WN * EPILOGUE_SCRATCH_FLOATS * 4,
+                  "epilogue scratch fits in the panels' LDS");
+    gemm16_epilogue<Cfg, EPI>(g, acc, reinterpret_cast<float *>(lds) + wave * EPILOGUE_SCRATCH_FLOATS, i0, j0, z, tile_n);
 }
 
 template <class Cfg, bool A_KC, bool B_KC, int EPI>

@@ -131,6 +131,56 @@ __global__ __launch_bounds__(THREADS) void softmax_ce_long_kernel(float *__restr
     }
 }
 
+// Output stage of the bf16-operand path, after an output-layer product that left the logits as bf16 (Z16, row
+// stride ldz, a multiple of 8 so that rows are 16-byte aligned) together with per-row statistics: for each of
+// `groups` column groups (max, sum of exp(z - max)) of the fp32 logits, and the fp32 logit of the label.
+// One wavefront per pattern, four patterns per workgroup:
+//     lse = ln sum_c exp(z_c) joined from the groups;  row_loss[r] = lse - z_label  (0 if the label is out of range)
+//     row_lse[r] = lse (+inf for an ignored pattern: exp(z - inf) = 0 gives its zero delta)
+//     WRITE_DELTA: z_c <- bf16(exp(z_c - lse) - [c == label]) in place (zero row if ignored; padding columns zero)
+template <bool WRITE_DELTA>
+__global__ __launch_bounds__(256) void softmax16_finish_kernel(u16 *__restrict__ Z16, int ldz, int n, int rows,
+                                                               const float2 *__restrict__ stats, int groups,
+                                                               const float *__restrict__ label_logit,
+                                                               const int32_t *__restrict__ labels,
+                                                               float *__restrict__ row_loss,
+                                                               float *__restrict__ row_lse)
+{
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;                       // whole wavefronts leave; no workgroup barrier below
+    const int y = labels[r];
+    const bool labelled = (y >= 0 && y < n);
+    const float2 *st = stats + (size_t)r * groups;
+    float m = -INFINITY;
+    for (int gI = lane; gI < groups; gI += 64) m = fmaxf(m, st[gI].x);
+    m = wave_max(m);
+    float s = 0.f;
+    for (int gI = lane; gI < groups; gI += 64) {
+        const float2 p = st[gI];
+        s += p.x == m ? p.y : p.y * __expf(p.x - m);
+    }
+    s = wave_sum(s);
+    const float lse = m + __logf(s);
+    if (lane == 0) {
+        row_loss[r] = labelled ? lse - label_logit[r] : 0.f;
+        if (row_lse) row_lse[r] = labelled ? lse : INFINITY;
+    }
+    if (!WRITE_DELTA) return;
+    u16 *z = Z16 + (size_t)r * ldz;
+    for (int c0 = lane * 8; c0 < ldz; c0 += 64 * 8) {
+        const u16x8 raw = *reinterpret_cast<const u16x8 *>(z + c0);
+        u16x8 out;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int c = c0 + e;
+            const float d = __expf(bf16_to_f32(raw[e]) - lse) - (c == y ? 1.0f : 0.0f);
+            out[e] = (labelled && c < n) ? f32_to_bf16(d) : (u16)0;
+        }
+        *reinterpret_cast<u16x8 *>(z + c0) = out;
+    }
+}
+
 // Output stage of the paper's own form (tanh outputs, summed squared error against dense targets): one workgroup
 // per pattern; Y holds the outputs y = tanh(z) (written by the output-layer product's epilogue).
 //     row_loss[r] = sum_c (y_c - t_c)^2,   y_c <- 2 (y_c - t_c) (1 - y_c^2)   (in place, if WRITE_DELTA)

@@ -429,21 +429,40 @@ hipError_t launch16_one(const Gemm16Args &a, int splits, hipStream_t s)
 
 inline bool rows_16b_aligned(const void *p, int ld) { return ((uintptr_t)p & 15) == 0 && (ld & 7) == 0; }
 
-// The combinations the MLP gradient needs: NN with bias+tanh / bias, NT with the tanh' mask, NT and TN partials,
-// TN with alpha/beta.
+// Columns of C one statistics group of the output-layer epilogue covers: the wavefront sub-tile width of the shape.
+inline int stat_group_width(Cfg16Id id)
+{
+    switch (id) {
+        case CFG16_128: return T16_128::WTN;
+        case CFG16_256: return T16_256::WTN;
+        case CFG16_256x256: return T16_256x256::WTN;
+        default: return T16_64::WTN;
+    }
+}
+
+// The combinations the MLP gradient needs: NN with bias+tanh / bias / bias + softmax statistics, NT with the tanh'
+// mask, NT and TN partials, TN with alpha/beta.
 hipError_t launch_gemm16(const Gemm16Plan &p, bool a_kc, bool b_kc, int epi, Gemm16Args a, hipStream_t s)
 {
     a.tiles_m = p.tiles_m;
     a.tiles_n = p.tiles_n;
     a.kchunk = p.kchunk;
     a.aligned = rows_16b_aligned(a.A, a.lda) && rows_16b_aligned(a.B, a.ldb);
-    const bool c_bf16 = epi == EPI_BIAS_TANH || epi == EPI_TANHGRAD;
+    const bool c_bf16 = epi == EPI_BIAS_TANH || epi == EPI_TANHGRAD || epi == EPI_BIAS_STATS;
     a.c_vec = ((uintptr_t)a.C & 15) == 0 && (a.ldc % (c_bf16 ? 8 : 4)) == 0;
     a.aux_vec = a.aux != nullptr && rows_16b_aligned(a.aux, a.ldaux);
     auto go = [&](auto cfg) -> hipError_t {
         using Cfg = decltype(cfg);
         if (epi == EPI_BIAS_TANH && a_kc && !b_kc) return launch16_one<Cfg, true, false, EPI_BIAS_TANH>(a, p.splits, s);
         if (epi == EPI_BIAS && a_kc && !b_kc) return launch16_one<Cfg, true, false, EPI_BIAS>(a, p.splits, s);
+        if ((epi == EPI_BIAS_STATS || epi == EPI_STATS_ONLY) && a_kc && !b_kc) {
+            // one statistics group per wavefront column; the logits' rows must be 16-byte aligned
+            if (a.stat_groups != (a.N + Cfg::WTN - 1) / Cfg::WTN || !a.stats || !a.label_logit || !a.labels ||
+                (epi == EPI_BIAS_STATS && !a.c_vec))
+                return hipErrorInvalidValue;
+            return epi == EPI_BIAS_STATS ? launch16_one<Cfg, true, false, EPI_BIAS_STATS>(a, p.splits, s)
+                                         : launch16_one<Cfg, true, false, EPI_STATS_ONLY>(a, p.splits, s);
+        }
         if (epi == EPI_TANHGRAD && a_kc && b_kc) return launch16_one<Cfg, true, true, EPI_TANHGRAD>(a, p.splits, s);
         if (epi == EPI_PARTIAL && a_kc && b_kc) return launch16_one<Cfg, true, true, EPI_PARTIAL>(a, p.splits, s);
         if (epi == EPI_PARTIAL && !a_kc && !b_kc) return launch16_one<Cfg, false, false, EPI_PARTIAL>(a, p.splits, s);
@@ -466,7 +485,7 @@ struct MlpLayout {
     int ldw1p, ldw2p;               // bf16 path: row strides of the 16-byte aligned copies of W1 and W2
     size_t floats_pa, floats_pb;    // split-k partial regions: A (dW2, then dW1) and B (hidden delta)
     size_t off_h, off_z, off_da1, off_rowloss, off_pa, off_pb, bytes;
-    size_t off_do16, off_w1p, off_w2p;   // bf16 path only
+    size_t off_do16, off_w1p, off_w2p, off_zlab, off_lse;   // bf16 path only
 };
 
 struct SlabPlans {
@@ -516,7 +535,9 @@ MlpLayout mlp_layout(const ulsnn_mlp_desc *d, int batch)
     L.floats_pb = std::max(mn4, std::min(PARTIAL_CAP_FLOATS, 16 * mn4));
     size_t off = 0;
     L.off_h = off;        off += round_up((size_t)L.slab * L.ldh * act, 256);
-    L.off_z = off;        off += round_up((size_t)L.slab * L.ldz * 4, 256);
+    // fp32: the logits / output delta.  bf16: the softmax statistics of the output layer's epilogue, one
+    // (max, sum) pair per row and group of at least 32 columns (the logits themselves live at off_do16)
+    L.off_z = off;        off += round_up(bf16 ? (size_t)L.slab * (L.ldz / 32) * sizeof(float2) : (size_t)L.slab * L.ldz * 4, 256);
     L.off_da1 = off;      off += round_up((size_t)L.slab * L.ldh * act, 256);
     L.off_rowloss = off;  off += round_up((size_t)L.slab * 4, 256);
     L.off_pa = off;       off += round_up(L.floats_pa * 4, 256);
@@ -525,6 +546,8 @@ MlpLayout mlp_layout(const ulsnn_mlp_desc *d, int batch)
         L.off_do16 = off; off += round_up((size_t)L.slab * L.ldz * 2, 256);
         L.off_w1p = off;  off += round_up((size_t)d->n_in * L.ldw1p * 2, 256);
         L.off_w2p = off;  off += round_up((size_t)d->n_hid * L.ldw2p * 2, 256);
+        L.off_zlab = off; off += round_up((size_t)L.slab * 4, 256);
+        L.off_lse = off;  off += round_up((size_t)L.slab * 4, 256);
     }
     L.bytes = std::max(off, small_net_bytes(d, batch));
     return L;
@@ -618,25 +641,25 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, con
                                accumulate, ev);
     const float *W1 = (const float *)W1v, *W2 = (const float *)W2v, *X = (const float *)Xv;
 
-    // small network, small batch, softmax form, no stage timing asked for: two launches instead of nine
-    if (!ev && !task.targets && small_net_shape(d, batch)) {
+    // small network, small batch, no stage timing asked for: two launches instead of nine
+    if (!ev && small_net_shape(d, batch)) {
         const size_t need = mlp_layout(d, batch).bytes;
         if (!d->workspace || ((uintptr_t)d->workspace & 255) || d->workspace_bytes < need) return ULSNN_ERR_WORKSPACE;
         SmallNetArgs a{};
         a.n_in = n_in; a.n_hid = n_hid; a.n_out = n_out; a.batch = batch;
-        a.W1 = W1; a.W2 = W2; a.b1 = d->b1; a.b2 = d->b2; a.X = X; a.labels = task.labels;
+        a.W1 = W1; a.W2 = W2; a.b1 = d->b1; a.b2 = d->b2; a.X = X; a.labels = task.labels; a.targets = task.targets;
         a.partial = (float *)d->workspace; a.stride = small_net_stride(d); a.backward = task.backward ? 1 : 0;
         const int groups = (batch + SMALL_ROWS - 1) / SMALL_ROWS;
         const size_t lds = (size_t)small_net_lds_floats(n_in, n_hid, n_out) * sizeof(float);
-        hipLaunchKernelGGL(small_net_kernel, dim3(groups), dim3(256), lds, s, a);
         SmallReduceArgs r{};
         r.partial = a.partial; r.stride = a.stride; r.groups = groups;
         r.n1 = n_in * n_hid; r.n2 = n_hid * n_out; r.n_hid = n_hid; r.n_out = n_out;
         r.dW1 = task.backward ? dW1 : nullptr; r.dW2 = task.backward ? dW2 : nullptr;
         r.db1 = task.backward ? d->db1 : nullptr; r.db2 = task.backward ? d->db2 : nullptr;
         r.loss = loss; r.beta = accumulate ? 1.0f : 0.0f;
-        const int total = r.n1 + r.n2 + n_hid + n_out + 1;
-        hipLaunchKernelGGL(small_reduce_kernel, dim3(task.backward ? (total + 255) / 256 : 1), dim3(256), 0, s, r);
+        const int total = task.backward ? r.n1 + r.n2 + n_hid + n_out + 1 : 1;
+        hipLaunchKernelGGL(small_net_kernel, dim3(groups), dim3(256), lds, s, a);
+        hipLaunchKernelGGL(small_reduce_kernel, dim3((total / 4 + 256) / 256), dim3(256), 0, s, r);
         HIP_TRY(hipGetLastError());
         return ULSNN_OK;
     }
@@ -794,8 +817,10 @@ int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const
         return ULSNN_ERR_WORKSPACE;
     char *ws = (char *)d->workspace;
     u16 *H = (u16 *)(ws + L.off_h);
-    float *Z = (float *)(ws + L.off_z);
-    u16 *dO = (u16 *)(ws + L.off_do16);
+    float2 *stats = (float2 *)(ws + L.off_z);
+    u16 *dO = (u16 *)(ws + L.off_do16);          // the logits as bf16, then the output delta in their place
+    float *zlab = (float *)(ws + L.off_zlab);
+    float *row_lse = (float *)(ws + L.off_lse);
     u16 *dA1 = (u16 *)(ws + L.off_da1);
     float *row_loss = (float *)(ws + L.off_rowloss);
     float *part_a = (float *)(ws + L.off_pa);
@@ -839,29 +864,24 @@ int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const
         HIP_TRY(launch_gemm16(p1, true, false, EPI_BIAS_TANH, a, s));
         MARK(1);
 
-        // Z = H W2 + b2, fp32
+        // Z = H W2 + b2 rounded to bf16, with the softmax statistics of every row taken from the fp32 accumulators
+        // in the product's epilogue (an error-only call writes the statistics alone)
         a = Gemm16Args{};
-        a.A = H; a.lda = L.ldh; a.B = W2; a.ldb = ldw2; a.C = Z; a.ldc = L.ldz;
+        a.A = H; a.lda = L.ldh; a.B = W2; a.ldb = ldw2; a.C = dO; a.ldc = L.ldz;
         a.M = rows; a.N = n_out; a.K = n_hid; a.alpha = 1.f; a.bias = d->b2;
-        HIP_TRY(launch_gemm16(p2, true, false, EPI_BIAS, a, s));
+        a.stats = stats; a.label_logit = zlab; a.labels = ys;
+        const int sgw = stat_group_width(p2.cfg);
+        a.stat_groups = (n_out + sgw - 1) / sgw;
+        HIP_TRY(launch_gemm16(p2, true, false, task.backward ? EPI_BIAS_STATS : EPI_STATS_ONLY, a, s));
         MARK(2);
 
-        // dO = softmax(Z) - onehot in bf16 (for a gradient); loss (+)= sum of the row losses
-        if (n_out <= 256 * 16) {
-            if (task.backward)
-                hipLaunchKernelGGL((softmax_ce_kernel<256, 16, true>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out, ys,
-                                   row_loss, dO, L.ldz);
-            else
-                hipLaunchKernelGGL((softmax_ce_kernel<256, 16, false, false>), dim3(rows), dim3(256), 0, s, Z, L.ldz,
-                                   n_out, ys, row_loss, (u16 *)nullptr, 0);
-        } else {
-            if (task.backward)
-                hipLaunchKernelGGL((softmax_ce_long_kernel<256, true>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out,
-                                   ys, row_loss, dO, L.ldz);
-            else
-                hipLaunchKernelGGL((softmax_ce_long_kernel<256, false, false>), dim3(rows), dim3(256), 0, s, Z, L.ldz,
-                                   n_out, ys, row_loss, (u16 *)nullptr, 0);
-        }
+        // row losses, and for a gradient dO = softmax(Z) - onehot in bf16 in place of the logits; loss (+)= sum
+        if (task.backward)
+            hipLaunchKernelGGL(softmax16_finish_kernel<true>, dim3((rows + 3) / 4), dim3(256), 0, s, dO, L.ldz, n_out,
+                               rows, (const float2 *)stats, a.stat_groups, (const float *)zlab, ys, row_loss, row_lse);
+        else
+            hipLaunchKernelGGL(softmax16_finish_kernel<false>, dim3((rows + 3) / 4), dim3(256), 0, s, dO, L.ldz, n_out,
+                               rows, (const float2 *)stats, a.stat_groups, (const float *)zlab, ys, row_loss, row_lse);
         hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, row_loss, (long long)rows, loss, beta);
         HIP_TRY(hipGetLastError());
         MARK(3);
@@ -1219,100 +1239,95 @@ int ulsnn_mlp_line_search(const ulsnn_mlp_desc *desc, float *W1, float *W2, cons
     float *T1 = (float *)(base + L.off_w1), *T2 = (float *)(base + L.off_w2);
     float *G1 = (float *)(base + L.off_g1), *G2 = (float *)(base + L.off_g2);
     double *partial = (double *)(base + L.off_vec);
-    float *scal = (float *)(base + L.off_scalars);   // [0] loss, [1] g1.d1, [2] g2.d2
+    static_assert(sizeof(LineSearchScalars) <= 256, "scalars fit their workspace slot");
+    LineSearchScalars *scal = (LineSearchScalars *)(base + L.off_scalars);
     hipStream_t s = (hipStream_t)desc->hip_stream;
     ulsnn_mlp_desc sub = *desc;
     sub.workspace = base;
     sub.workspace_bytes = L.mlp_bytes;
     sub.accumulate = 0;
     const int nsub = std::min(bracket_batch, batch);
-    int n_err = 0, n_grad = 0;
+    const unsigned wgrid = grid_for(L.n1 + L.n2);
 
-    // weights at step alpha: the caller's own for alpha == 0, else T = W + alpha d
-    auto weights_at = [&](double alpha, const float *&w1, const float *&w2) -> hipError_t {
-        if (alpha == 0.0) {
+    // weights at step alpha: the caller's own for alpha == 0, else T = W + alpha d (alpha from the host, or, with
+    // alpha_dev, a step the device chose)
+    auto weights_at = [&](double alpha, const float *alpha_dev, const float *&w1, const float *&w2) -> hipError_t {
+        if (!alpha_dev && alpha == 0.0) {
             w1 = W1; w2 = W2;
             return hipSuccess;
         }
-        hipLaunchKernelGGL(add_scaled_kernel, dim3(grid_for(L.n1)), dim3(256), 0, s, L.n1, (const float *)W1,
-                           (float)alpha, d1, T1);
-        hipLaunchKernelGGL(add_scaled_kernel, dim3(grid_for(L.n2)), dim3(256), 0, s, L.n2, (const float *)W2,
-                           (float)alpha, d2, T2);
+        hipLaunchKernelGGL(add_scaled2_kernel, dim3(wgrid), dim3(256), 0, s, L.n1, (const float *)W1, d1, T1, L.n2,
+                           (const float *)W2, d2, T2, (float)alpha, alpha_dev);
         w1 = T1; w2 = T2;
         return hipGetLastError();
     };
-    // E(W + alpha d) over all `batch` patterns (one error evaluation, section 6.2)
-    auto error_at = [&](double alpha, double &e) -> int {
+    // E(W + alpha d) over all `batch` patterns (one error evaluation, section 6.2), left in *out on the device
+    auto error_at = [&](double alpha, const float *alpha_dev, float *out) -> int {
         const float *w1, *w2;
-        HIP_TRY(weights_at(alpha, w1, w2));
-        const int rc = mlp_grad_impl(&sub, w1, w2, X, MlpTask{labels, nullptr, false}, batch, nullptr, nullptr, scal,
-                                     false);
-        if (rc != ULSNN_OK) return rc;
-        float h = 0.f;
-        HIP_TRY(hipMemcpyAsync(&h, scal, sizeof(float), hipMemcpyDeviceToHost, s));
-        HIP_TRY(hipStreamSynchronize(s));
-        e = (double)h;
-        ++n_err;
-        return ULSNN_OK;
+        HIP_TRY(weights_at(alpha, alpha_dev, w1, w2));
+        return mlp_grad_impl(&sub, w1, w2, X, MlpTask{labels, nullptr, false}, batch, nullptr, nullptr, out, false);
     };
-    // grad E_sub(W + alpha d) . d on the first nsub patterns: only its sign is used
-    auto slope_at = [&](double alpha, double &sl) -> int {
+    // grad E_sub(W + alpha d) . d on the first nsub patterns, left in *out on the device: only its sign is used
+    auto slope_at = [&](double alpha, float *out) -> int {
         const float *w1, *w2;
-        HIP_TRY(weights_at(alpha, w1, w2));
-        const int rc = mlp_grad_impl(&sub, w1, w2, X, MlpTask{labels, nullptr, true}, nsub, G1, G2, scal, false);
+        HIP_TRY(weights_at(alpha, nullptr, w1, w2));
+        const int rc = mlp_grad_impl(&sub, w1, w2, X, MlpTask{labels, nullptr, true}, nsub, G1, G2, &scal->E[4], false);
         if (rc != ULSNN_OK) return rc;
-        HIP_TRY(launch_dot(L.n1, G1, d1, scal + 1, partial, s));
-        HIP_TRY(launch_dot(L.n2, G2, d2, scal + 2, partial, s));
-        float h[2] = {0.f, 0.f};
-        HIP_TRY(hipMemcpyAsync(h, scal + 1, 2 * sizeof(float), hipMemcpyDeviceToHost, s));
-        HIP_TRY(hipStreamSynchronize(s));
-        sl = (double)h[0] + (double)h[1];
-        ++n_grad;
+        const unsigned nb = vec_grid(L.n1 + L.n2);
+        hipLaunchKernelGGL(dot2_partial_kernel, dim3(nb), dim3(256), 0, s, L.n1, (const float *)G1, d1, L.n2,
+                           (const float *)G2, d2, partial);
+        hipLaunchKernelGGL(dot_final_kernel<false>, dim3(1), dim3(256), 0, s, (const double *)partial, (int)nb, out);
+        HIP_TRY(hipGetLastError());
         return ULSNN_OK;
     };
 
+    // The host reads device scalars only where it must decide what to launch next: once per group of GROUP
+    // bracketing steps (the steps of a group are evaluated whether or not an earlier one of the group already
+    // closed the bracket: a few spare evaluations on the small subset instead of a round trip each), and once at
+    // the end.  Vertex, comparison of the errors and the weight update use steps the device computes.
+    constexpr int GROUP = 8;                          // largest group; the first two hold 2 and 4 steps
     int rc;
-    double e0 = 0.0;
-    if ((rc = error_at(0.0, e0)) != ULSNN_OK) return rc;
+    if ((rc = error_at(0.0, nullptr, &scal->E[0])) != ULSNN_OK) return rc;
     double lo = 0.0, hi = alpha0, prev = 0.0;
-    for (int k = 0; k <= max_doublings; ++k) {
-        hi = (double)alpha0 * std::ldexp(1.0, k);
-        lo = prev;
-        double sl = 0.0;
-        if ((rc = slope_at(hi, sl)) != ULSNN_OK) return rc;
-        if (sl >= 0.0) break;
-        prev = hi;
+    int n_grad = 0;
+    bool closed = false;
+    int size = 2;
+    for (int k0 = 0; k0 <= max_doublings && !closed; k0 += size, size = std::min(2 * size, GROUP)) {
+        const int cnt = std::min(size, max_doublings + 1 - k0);
+        for (int j = 0; j < cnt; ++j)
+            if ((rc = slope_at((double)alpha0 * std::ldexp(1.0, k0 + j), &scal->slope[j])) != ULSNN_OK) return rc;
+        float h[GROUP] = {};
+        HIP_TRY(hipMemcpyAsync(h, scal->slope, cnt * sizeof(float), hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        for (int j = 0; j < cnt; ++j) {
+            hi = (double)alpha0 * std::ldexp(1.0, k0 + j);
+            lo = prev;
+            ++n_grad;
+            if (h[j] >= 0.0f) { closed = true; break; }
+            prev = hi;
+        }
     }
+    const bool lo_zero = lo == 0.0;
     const double mid = 0.5 * (lo + hi);
-    double e_lo = e0, e_mid = 0.0, e_hi = 0.0;
-    if (lo != 0.0 && (rc = error_at(lo, e_lo)) != ULSNN_OK) return rc;
-    if ((rc = error_at(mid, e_mid)) != ULSNN_OK) return rc;
-    if ((rc = error_at(hi, e_hi)) != ULSNN_OK) return rc;
-    double best_a = lo, best_e = e_lo;
-    if (e_mid < best_e) { best_a = mid; best_e = e_mid; }
-    if (e_hi < best_e) { best_a = hi; best_e = e_hi; }
-    const double curv = e_lo - 2.0 * e_mid + e_hi;
-    if (curv > 0.0) {
-        const double h = 0.5 * (hi - lo);
-        double q = mid - h * (e_hi - e_lo) / (2.0 * curv);
-        q = std::min(std::max(q, lo), hi);
-        double e_q = 0.0;
-        if ((rc = error_at(q, e_q)) != ULSNN_OK) return rc;
-        if (e_q < best_e) { best_a = q; best_e = e_q; }
-    }
-    if (best_a != 0.0) {
-        hipLaunchKernelGGL(add_scaled_kernel, dim3(grid_for(L.n1)), dim3(256), 0, s, L.n1, (const float *)W1,
-                           (float)best_a, d1, W1);
-        hipLaunchKernelGGL(add_scaled_kernel, dim3(grid_for(L.n2)), dim3(256), 0, s, L.n2, (const float *)W2,
-                           (float)best_a, d2, W2);
-        HIP_TRY(hipGetLastError());
-    }
-    result->alpha = (float)best_a;
-    result->loss = (float)best_e;
-    result->loss0 = (float)e0;
+    if (!lo_zero && (rc = error_at(lo, nullptr, &scal->E[1])) != ULSNN_OK) return rc;
+    if ((rc = error_at(mid, nullptr, &scal->E[2])) != ULSNN_OK) return rc;
+    if ((rc = error_at(hi, nullptr, &scal->E[3])) != ULSNN_OK) return rc;
+    hipLaunchKernelGGL(ls_vertex_kernel, dim3(1), dim3(1), 0, s, scal, (int)lo_zero, (float)lo, (float)hi);
+    HIP_TRY(hipGetLastError());
+    if ((rc = error_at(0.0, &scal->q, &scal->E[4])) != ULSNN_OK) return rc;   // at the vertex (at mid again if not convex)
+    hipLaunchKernelGGL(ls_pick_kernel, dim3(1), dim3(1), 0, s, scal, (int)lo_zero, (float)lo, (float)hi);
+    hipLaunchKernelGGL(add_scaled2_kernel, dim3(wgrid), dim3(256), 0, s, L.n1, (const float *)W1, d1, W1, L.n2,
+                       (const float *)W2, d2, W2, 0.0f, (const float *)&scal->alpha);
+    HIP_TRY(hipGetLastError());
+    LineSearchScalars host{};
+    HIP_TRY(hipMemcpyAsync(&host, scal, sizeof(host), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    result->alpha = host.alpha;
+    result->loss = host.loss;
+    result->loss0 = host.E[0];
     result->bracket_lo = (float)lo;
     result->bracket_hi = (float)hi;
-    result->error_evaluations = n_err;
+    result->error_evaluations = 1 + (lo_zero ? 0 : 1) + 2 + (host.convex ? 1 : 0);   // the algorithm's own count
     result->gradient_evaluations = n_grad;
     return ULSNN_OK;
 }

@@ -79,6 +79,74 @@ __global__ __launch_bounds__(256) void add_scaled_kernel(size_t n, const float *
         out[i] = w[i] + alpha * x[i];
 }
 
+// Two-segment forms for the line search, whose parameter vector is the pair (W1, W2): one launch instead of two.
+// out = w + alpha x on both segments; alpha comes from device memory when alpha_dev is not null (a step the device
+// itself chose), else from the argument.
+__global__ __launch_bounds__(256) void add_scaled2_kernel(size_t n1, const float *w1, const float *__restrict__ x1,
+                                                          float *o1, size_t n2, const float *w2,
+                                                          const float *__restrict__ x2, float *o2, float alpha,
+                                                          const float *__restrict__ alpha_dev)
+{
+    const float a = alpha_dev ? *alpha_dev : alpha;
+    if (a == 0.f && o1 == w1 && o2 == w2) return;      // in-place update by a zero step: nothing changes
+    const size_t n = n1 + n2;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        if (i < n1) o1[i] = w1[i] + a * x1[i];
+        else o2[i - n1] = w2[i - n1] + a * x2[i - n1];
+    }
+}
+
+// partial[b] = this workgroup's share of x1.y1 + x2.y2 (double); dot_final_kernel<false> adds the shares.
+__global__ __launch_bounds__(256) void dot2_partial_kernel(size_t n1, const float *__restrict__ x1,
+                                                           const float *__restrict__ y1, size_t n2,
+                                                           const float *__restrict__ x2, const float *__restrict__ y2,
+                                                           double *__restrict__ partial)
+{
+    __shared__ double red[4];
+    double a = 0.0;
+    const size_t n = n1 + n2;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256)
+        a += i < n1 ? (double)x1[i] * (double)y1[i] : (double)x2[i - n1] * (double)y2[i - n1];
+    a = block_sum_256(a, red);
+    if (threadIdx.x == 0) partial[blockIdx.x] = a;
+}
+
+// Decisions of the line search taken on the device, so that the host need not read the errors one by one.
+// E[0] = E(W), E[1..3] = E at lo, mid, hi (E[1] unused when lo == 0), E[4] = E at the vertex.
+struct LineSearchScalars {
+    float E[5];
+    float q;            // vertex of the parabola through (lo, mid, hi), clamped to the bracket; mid if not convex
+    int convex;
+    float alpha, loss;  // the step chosen and the error there
+    float slope[16];    // slopes of one group of bracketing steps
+};
+
+__global__ void ls_vertex_kernel(LineSearchScalars *s, int lo_is_zero, float lo_f, float hi_f)
+{
+    const double lo = lo_f, hi = hi_f, mid = 0.5 * (lo + hi);
+    const double e_lo = lo_is_zero ? s->E[0] : s->E[1], e_mid = s->E[2], e_hi = s->E[3];
+    const double curv = e_lo - 2.0 * e_mid + e_hi;
+    double q = mid;
+    if (curv > 0.0) {
+        const double h = 0.5 * (hi - lo);
+        q = mid - h * (e_hi - e_lo) / (2.0 * curv);
+        q = q < lo ? lo : (q > hi ? hi : q);
+    }
+    s->q = (float)q;
+    s->convex = curv > 0.0 ? 1 : 0;
+}
+
+__global__ void ls_pick_kernel(LineSearchScalars *s, int lo_is_zero, float lo_f, float hi_f)
+{
+    const double lo = lo_f, hi = hi_f, mid = 0.5 * (lo + hi);
+    double best_a = lo, best_e = lo_is_zero ? s->E[0] : s->E[1];
+    if ((double)s->E[2] < best_e) { best_a = mid; best_e = s->E[2]; }
+    if ((double)s->E[3] < best_e) { best_a = hi; best_e = s->E[3]; }
+    if (s->convex && (double)s->E[4] < best_e) { best_a = s->q; best_e = s->E[4]; }
+    s->alpha = (float)best_a;
+    s->loss = (float)best_e;
+}
+
 // Measurement aid: one wavefront reads the shader cycle counter and the constant-rate wall clock until
 // `wall_ticks` ticks of the latter have passed (or `max_iterations` readings, so that it always ends), and writes
 // out[0] = shader cycles, out[1] = wall-clock ticks that elapsed in between.  Launched beside a workload, the

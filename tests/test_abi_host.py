@@ -196,8 +196,10 @@ def test_bf16_workspace_is_separate_query():
     w32 = ulsnn.mlp_grad_workspace_bytes(400, 480, 3203, 4096, 0)
     w16 = ulsnn.mlp_grad_workspace_bytes(400, 480, 3203, 4096, 1)
     assert w16 > 0 and w16 != w32
-    # bf16 path: H and dA1 take half the room, dO is kept beside the fp32 logits, plus aligned weight copies
-    assert w16 >= 4096 * (3232 * 4 + 3232 * 2 + 2 * 480 * 2) + 480 * 3208 * 2
+    # bf16 path: H, dA1 and the logits / output delta are 2 bytes wide, the softmax statistics of the output
+    # layer's epilogue (8 bytes per row and 32 columns) stand in for fp32 logits, plus aligned weight copies
+    assert w16 >= 4096 * (3232 * 2 + 101 * 8 + 2 * 480 * 2) + 480 * 3208 * 2
+    assert w16 < w32
 
 
 def test_plan_description():

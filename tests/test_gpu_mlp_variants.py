@@ -71,7 +71,9 @@ def _mse_problem(shape, seed, batch):
 
 
 @pytest.mark.parametrize("shape,batch", [(si.MLP_SMALL, 256), (si.MlpShape(100, 130, 259, True), 300),
-                                         (si.MlpShape(17, 33, 5, True), 1), (si.MLP_JOCR, 2048)])
+                                         (si.MlpShape(17, 33, 5, True), 1), (si.MLP_JOCR, 2048),
+                                         (si.MlpShape(128, 64, 40, False), 1000),    # small-network path, two launches
+                                         (si.MLP_SMALL, 4097)])                      # one pattern too many for it
 def test_mse_gradient(shape, batch):
     W1, W2, b1, b2, X, T = _mse_problem(shape, 2, batch)
     ref = oracle.mlp_grad_mse(_np(W1), _np(W2), _np(X), _np(T), _np(b1), _np(b2))
@@ -91,6 +93,11 @@ def test_mse_gradient(shape, batch):
     only = ulsnn.mlp_mse(_dev(W1), _dev(W2), _dev(X), _dev(T), _dev(b1), _dev(b2))
     torch.cuda.synchronize()
     assert torch.equal(only, res.loss)
+    # a second call adding to the first: twice the gradient (and, on the small-network path, a ticket counter
+    # that the first call left at zero)
+    ulsnn.mlp_grad_mse(_dev(W1), _dev(W2), _dev(X), _dev(T), _dev(b1), _dev(b2), out=res, accumulate=True)
+    torch.cuda.synchronize()
+    assert _rel(res.dW2.cpu().numpy(), 2 * ref.dW2) <= 1e-4 and abs(res.loss.item() - 2 * ref.loss) <= 2e-5 * ref.loss
 
 
 def test_mse_matches_the_papers_matrix_identities():
