@@ -490,7 +490,20 @@ def main():
         r["frac_of_bf16_mfma_peak"] = round(r["gflops"] / 2.5e6, 4)
         r["workload"] = "same net, X/W/H/dO/dA1 in bf16, fp32 accumulate, batch 65536"
         result["bf16"] = r
-        del Xb, yb
+        # the squared-error form on the same operands (dense fp32 targets, 840 MB)
+        Wb1, Wb2, Xbb = W1.to(torch.bfloat16), W2.to(torch.bfloat16), Xb.to(torch.bfloat16)
+        Tb = si.mlp_targets(shape, SEED, 0, 65536, device=dev)
+        wsb = torch.empty(ulsnn.mlp_grad_workspace_bytes(shape.n_in, shape.n_hid, shape.n_out, 65536, 1),
+                          dtype=torch.uint8, device=dev)
+        settle(torch, lambda: ulsnn.mlp_grad_mse(Wb1, Wb2, Xbb, Tb, out=out, workspace=wsb), 0.1)
+        t1 = time.perf_counter()
+        for _ in range(5):
+            ulsnn.mlp_grad_mse(Wb1, Wb2, Xbb, Tb, out=out, workspace=wsb)
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t1) / 5
+        result["bf16"]["mse_grad"] = {"ms": round(sec * 1e3, 4),
+                                      "gflops": round(ulsnn.mlp_grad_flops(shape.n_in, shape.n_hid, shape.n_out, 65536) / sec / 1e9, 1)}
+        del Xb, yb, Tb, wsb, Xbb
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)

@@ -62,6 +62,18 @@ int ulsnn_sgemm(char transa, char transb, int m, int n, int k, float alpha, cons
                 const float *B, int ldb, float beta, float *C, int ldc, void *hip_stream);
 
 /*
+ * The same operation with scratch memory for a deterministic k split (section 3.1's product; a product with few
+ * tiles of C and a long k cannot fill 256 compute units otherwise).  The library's planner chooses tile shape and
+ * number of k slices (at most what `workspace` holds partial products for: slices * m * n * 4 bytes; with less than
+ * 2 * m * n * 4 bytes the call is ulsnn_sgemm); partial products are added in slice order, so the same call gives
+ * the same bits.  workspace: device memory, 256-byte aligned (ULSNN_ERR_WORKSPACE otherwise), contents undefined on
+ * return; may be NULL with workspace_bytes == 0.  Everything else as ulsnn_sgemm.
+ */
+int ulsnn_sgemm_ws(char transa, char transb, int m, int n, int k, float alpha, const float *A, int lda,
+                   const float *B, int ldb, float beta, float *C, int ldc, void *workspace, size_t workspace_bytes,
+                   void *hip_stream);
+
+/*
  * Description of the network and of one gradient call (everything the 8-argument call below cannot carry).
  *
  *   Network (section 4.1, with the weight matrices stored transposed with respect to the paper's W_ih, W_ho):
@@ -171,8 +183,9 @@ int ulsnn_mlp_loss(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, c
  * dW1 and dW2 are the TRUE derivatives of E.  In the paper's notation (Y_Delta = (1 - Y**Y)**(T - Y),
  * grad_ho = Y_Delta^T * H, grad_ih = H_Delta^T * X, W_ho = W2^T, W_ih = W1^T): dW2 = -2 grad_ho^T and
  * dW1 = -2 grad_ih^T; the paper's "gradient" is an ascent direction of -E/2.
- * fp32 operands only (operand_dtype 1 returns ULSNN_ERR_UNSUPPORTED); everything else as ulsnn_mlp_grad.
- * ulsnn_mlp_mse is the error-only form (E alone).
+ * Operands fp32 or bf16 (desc->operand_dtype as for ulsnn_mlp_grad; T is fp32 in both cases; with bf16 operands the
+ * output stage runs inside the output layer's epilogue: E is summed from the fp32 outputs, dZ is stored as bf16).
+ * Everything else as ulsnn_mlp_grad.  ulsnn_mlp_mse is the error-only form (E alone).
  */
 int ulsnn_mlp_grad_mse(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, const void *X, const float *T,
                        int batch, float *dW1, float *dW2, float *loss);

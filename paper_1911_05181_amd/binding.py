@@ -56,6 +56,8 @@ def load():
     vp, i, f = C.c_void_p, C.c_int, C.c_float
     L.ulsnn_sgemm.argtypes = [C.c_char, C.c_char, i, i, i, f, vp, i, vp, i, f, vp, i, vp]
     L.ulsnn_sgemm.restype = i
+    L.ulsnn_sgemm_ws.argtypes = [C.c_char, C.c_char, i, i, i, f, vp, i, vp, i, f, vp, i, vp, C.c_size_t, vp]
+    L.ulsnn_sgemm_ws.restype = i
     L.ulsnn_mlp_grad_workspace_bytes.argtypes = [C.POINTER(_MlpDesc), i]
     L.ulsnn_mlp_grad_workspace_bytes.restype = C.c_size_t
     L.ulsnn_mlp_grad.argtypes = [C.POINTER(_MlpDesc), vp, vp, vp, vp, i, vp, vp, vp]
@@ -233,6 +235,21 @@ def sgemm(transa: str, transb: str, m: int, n: int, k: int, alpha: float, A: tor
                             beta, _ptr(Cmat), ldc, _stream(stream))
     if rc:
         raise UlsnnError(rc, "ulsnn_sgemm")
+
+
+def sgemm_ws(transa: str, transb: str, m: int, n: int, k: int, alpha: float, A: torch.Tensor, lda: int,
+             B: torch.Tensor, ldb: int, beta: float, Cmat: torch.Tensor, ldc: int, workspace: torch.Tensor,
+             stream=None) -> None:
+    """ulsnn_sgemm_ws: SGEMM that may split k into as many slices as `workspace` holds partial products for."""
+    _check_sgemm_tensors(transa, transb, m, n, k, alpha, A, lda, B, ldb, Cmat, ldc)
+    if workspace is not None and not (_on_gpu(workspace) and workspace.is_contiguous()):
+        raise TypeError("workspace must be a contiguous GPU tensor")
+    rc = load().ulsnn_sgemm_ws(transa.encode()[:1], transb.encode()[:1], m, n, k, alpha, _ptr(A), lda, _ptr(B), ldb,
+                               beta, _ptr(Cmat), ldc, _ptr(workspace),
+                               0 if workspace is None else workspace.numel() * workspace.element_size(),
+                               _stream(stream))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_sgemm_ws")
 
 
 def _vec_ws(workspace, device, stream=None):

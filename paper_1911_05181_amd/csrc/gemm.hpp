@@ -33,7 +33,10 @@ enum Epilogue {
     EPI_TANHGRAD = 4,   // C = acc * (1 - aux[i][j]^2)
     // bf16-operand kernel only: output layer with the softmax statistics of its rows taken in the epilogue
     EPI_BIAS_STATS = 5, // C = bf16(acc + bias[j]); per row and column group: max and sum of exp; the label's logit
-    EPI_STATS_ONLY = 6  // the same statistics, C not written (error-only evaluation)
+    EPI_STATS_ONLY = 6, // the same statistics, C not written (error-only evaluation)
+    // bf16-operand kernel only: output layer of the squared-error form, output stage taken in the epilogue
+    EPI_TANH_MSE = 7,   // y = tanh(acc + bias[j]); C = bf16(2 (y - t)(1 - y^2)); per row and column group: sum (y - t)^2
+    EPI_MSE_ONLY = 8    // the same sums, C not written
 };
 
 struct GemmArgs {

@@ -57,6 +57,10 @@ struct Gemm16Args {
     int stat_groups;       // tiles_n * WN of the launch's tile shape
     float *label_logit;
     const int32_t *labels;
+    // EPI_TANH_MSE / EPI_MSE_ONLY: dense fp32 targets t[i][j] (row stride ldt, 4-byte aligned); stats[..].x receives
+    // the group's sum of (y - t)^2
+    const float *targets;
+    int ldt;
     int aligned;           // 1: A and B rows are 16-byte aligned (fast vector fetch allowed)
     int c_vec;             // 1: rows of C are 16-byte aligned (pointer and ldc): row-wise vector epilogue
     int aux_vec;           // 1: rows of aux are 16-byte aligned
@@ -226,8 +230,9 @@ __device__ __forceinline__ void gemm16_epilogue(const Gemm16Args &g, floatx16 (&
                                                 const int tile_n)
 {
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
-    constexpr bool OUT_BF16 = (EPI == EPI_BIAS_TANH || EPI == EPI_TANHGRAD || EPI == EPI_BIAS_STATS);
-    constexpr bool STATS = (EPI == EPI_BIAS_STATS || EPI == EPI_STATS_ONLY);
+    constexpr bool OUT_BF16 = (EPI == EPI_BIAS_TANH || EPI == EPI_TANHGRAD || EPI == EPI_BIAS_STATS || EPI == EPI_TANH_MSE);
+    constexpr bool MSE = (EPI == EPI_TANH_MSE || EPI == EPI_MSE_ONLY);
+    constexpr bool STATS = (EPI == EPI_BIAS_STATS || EPI == EPI_STATS_ONLY || MSE);
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, h = lane >> 5;
@@ -264,7 +269,7 @@ __device__ __forceinline__ void gemm16_epilogue(const Gemm16Args &g, floatx16 (&
 #pragma unroll
             for (int pass = 0; pass < 2; ++pass) {
                 const int i = i0 + wrow + x * 32 + pass * 16 + srow;
-                lab[pass] = i < g.M ? g.labels[i] : -1;
+                lab[pass] = (!MSE && i < g.M) ? g.labels[i] : -1;
             }
 #pragma unroll
             for (int y = 0; y < TN; ++y) {
@@ -285,6 +290,29 @@ __device__ __forceinline__ void gemm16_epilogue(const Gemm16Args &g, floatx16 (&
                     const int i = i0 + wrow + x * 32 + row;
                     const int j = j0 + wcol + y * 32 + scol;
                     if (i >= g.M || j >= g.N) continue;
+                    if (MSE) {
+                        // the paper's output stage on the spot: no row-wide quantity is needed for the delta
+                        const float *tp = g.targets + (size_t)i * g.ldt + j;
+                        float t[8];
+                        if (j + 7 < g.N) {                       // two 16-byte loads (rows are only 4-byte aligned)
+                            const floatx4 t0 = load4_any_align(tp), t1 = load4_any_align(tp + 4);
+                            t[0] = t0.x; t[1] = t0.y; t[2] = t0.z; t[3] = t0.w;
+                            t[4] = t1.x; t[5] = t1.y; t[6] = t1.z; t[7] = t1.w;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) t[e] = j + e < g.N ? tp[e] : 0.f;
+                        }
+                        float err = 0.f;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const bool in = j + e < g.N;
+                            const float yv = tanh_f32(v[e] + ((g.bias && in) ? g.bias[j + e] : 0.f));
+                            const float diff = in ? yv - t[e] : 0.f;
+                            err += diff * diff;
+                            v[e] = 2.0f * diff * (1.0f - yv * yv);
+                        }
+                        rs[pass] += err;
+                    } else {
                     float bm = -INFINITY, zl = 0.f;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
@@ -300,7 +328,8 @@ __device__ __forceinline__ void gemm16_epilogue(const Gemm16Args &g, floatx16 (&
                     rs[pass] = (rm[pass] == nm ? rs[pass] : rs[pass] * __expf(rm[pass] - nm)) + bs;
                     rm[pass] = nm;
                     if (lab[pass] >= j && lab[pass] < j + 8 && lab[pass] < g.N) g.label_logit[i] = zl;
-                    if (EPI == EPI_BIAS_STATS) {
+                    }
+                    if (EPI == EPI_BIAS_STATS || EPI == EPI_TANH_MSE) {
                         u16x8 o;
 #pragma unroll
                         for (int e = 0; e < 8; ++e) o[e] = f32_to_bf16(v[e]);
@@ -320,11 +349,12 @@ __device__ __forceinline__ void gemm16_epilogue(const Gemm16Args &g, floatx16 (&
 #pragma unroll
                 for (int o = 1; o <= 2; o <<= 1) {
                     const float om = __shfl_xor(rm[pass], o, 64), os = __shfl_xor(rs[pass], o, 64);
-                    softmax_merge(rm[pass], rs[pass], om, os);
+                    if (MSE) rs[pass] += os;
+                    else softmax_merge(rm[pass], rs[pass], om, os);
                 }
                 const int i = i0 + wrow + x * 32 + pass * 16 + srow;
                 if ((lane & 3) == 0 && i < g.M && j0 + wcol < g.N)
-                    g.stats[(size_t)i * g.stat_groups + group] = make_float2(rm[pass], rs[pass]);
+                    g.stats[(size_t)i * g.stat_groups + group] = MSE ? make_float2(rs[pass], 0.f) : make_float2(rm[pass], rs[pass]);
             }
         }
         return;

@@ -181,6 +181,19 @@ __global__ __launch_bounds__(256) void softmax16_finish_kernel(u16 *__restrict__
     }
 }
 
+// Squared-error form of the bf16-operand path: the output layer's epilogue left, per row and column group, the sum
+// of (y - t)^2 in stats[..].x.  row_loss[r] = their sum in group order, one thread per pattern.
+__global__ __launch_bounds__(256) void mse16_finish_kernel(int rows, const float2 *__restrict__ stats, int groups,
+                                                           float *__restrict__ row_loss)
+{
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r >= rows) return;
+    const float2 *st = stats + (size_t)r * groups;
+    float s = 0.f;
+    for (int gI = 0; gI < groups; ++gI) s += st[gI].x;
+    row_loss[r] = s;
+}
+
 // Output stage of the paper's own form (tanh outputs, summed squared error against dense targets): one workgroup
 // per pattern; Y holds the outputs y = tanh(z) (written by the output-layer product's epilogue).
 //     row_loss[r] = sum_c (y_c - t_c)^2,   y_c <- 2 (y_c - t_c) (1 - y_c^2)   (in place, if WRITE_DELTA)

@@ -448,7 +448,7 @@ hipError_t launch_gemm16(const Gemm16Plan &p, bool a_kc, bool b_kc, int epi, Gem
     a.tiles_n = p.tiles_n;
     a.kchunk = p.kchunk;
     a.aligned = rows_16b_aligned(a.A, a.lda) && rows_16b_aligned(a.B, a.ldb);
-    const bool c_bf16 = epi == EPI_BIAS_TANH || epi == EPI_TANHGRAD || epi == EPI_BIAS_STATS;
+    const bool c_bf16 = epi == EPI_BIAS_TANH || epi == EPI_TANHGRAD || epi == EPI_BIAS_STATS || epi == EPI_TANH_MSE;
     a.c_vec = ((uintptr_t)a.C & 15) == 0 && (a.ldc % (c_bf16 ? 8 : 4)) == 0;
     a.aux_vec = a.aux != nullptr && rows_16b_aligned(a.aux, a.ldaux);
     auto go = [&](auto cfg) -> hipError_t {
@@ -462,6 +462,13 @@ hipError_t launch_gemm16(const Gemm16Plan &p, bool a_kc, bool b_kc, int epi, Gem
                 return hipErrorInvalidValue;
             return epi == EPI_BIAS_STATS ? launch16_one<Cfg, true, false, EPI_BIAS_STATS>(a, p.splits, s)
                                          : launch16_one<Cfg, true, false, EPI_STATS_ONLY>(a, p.splits, s);
+        }
+        if ((epi == EPI_TANH_MSE || epi == EPI_MSE_ONLY) && a_kc && !b_kc) {
+            if (a.stat_groups != (a.N + Cfg::WTN - 1) / Cfg::WTN || !a.stats || !a.targets || a.ldt < a.N ||
+                (epi == EPI_TANH_MSE && !a.c_vec))
+                return hipErrorInvalidValue;
+            return epi == EPI_TANH_MSE ? launch16_one<Cfg, true, false, EPI_TANH_MSE>(a, p.splits, s)
+                                       : launch16_one<Cfg, true, false, EPI_MSE_ONLY>(a, p.splits, s);
         }
         if (epi == EPI_TANHGRAD && a_kc && b_kc) return launch16_one<Cfg, true, true, EPI_TANHGRAD>(a, p.splits, s);
         if (epi == EPI_PARTIAL && a_kc && b_kc) return launch16_one<Cfg, true, true, EPI_PARTIAL>(a, p.splits, s);
@@ -808,7 +815,6 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, con
 int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const u16 *X, const MlpTask &task,
                     int batch, float *dW1, float *dW2, float *loss, bool accumulate, hipEvent_t *ev)
 {
-    if (task.targets) return ULSNN_ERR_UNSUPPORTED;   // the squared-error form exists for fp32 operands only
     hipStream_t s = (hipStream_t)d->hip_stream;
     const int n_in = d->n_in, n_hid = d->n_hid, n_out = d->n_out;
     const bool biases = d->b1 != nullptr;
@@ -848,7 +854,8 @@ int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const
         const int rows = std::min(L.slab, batch - r0);
         const float beta = (r0 > 0 || accumulate) ? 1.0f : 0.0f;
         const u16 *Xs = X + (size_t)r0 * n_in;
-        const int32_t *ys = task.labels + r0;
+        const int32_t *ys = task.labels ? task.labels + r0 : nullptr;
+        const float *ts = task.targets ? task.targets + (size_t)r0 * n_out : nullptr;
         const Gemm16Plan p1 = plan_gemm16(rows, n_hid, n_in, true, false, false, 0);
         const Gemm16Plan p2 = plan_gemm16(rows, n_out, n_hid, true, false, false, 0);
         const Gemm16Plan p3 = plan_gemm16(n_hid, n_out, rows, false, false, true, L.floats_pa);
@@ -869,14 +876,20 @@ int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const
         a = Gemm16Args{};
         a.A = H; a.lda = L.ldh; a.B = W2; a.ldb = ldw2; a.C = dO; a.ldc = L.ldz;
         a.M = rows; a.N = n_out; a.K = n_hid; a.alpha = 1.f; a.bias = d->b2;
-        a.stats = stats; a.label_logit = zlab; a.labels = ys;
+        a.stats = stats; a.label_logit = zlab; a.labels = ys; a.targets = ts; a.ldt = n_out;
         const int sgw = stat_group_width(p2.cfg);
         a.stat_groups = (n_out + sgw - 1) / sgw;
-        HIP_TRY(launch_gemm16(p2, true, false, task.backward ? EPI_BIAS_STATS : EPI_STATS_ONLY, a, s));
+        if (ts)   // the paper's output stage (tanh, squared error, delta) entirely in the epilogue
+            HIP_TRY(launch_gemm16(p2, true, false, task.backward ? EPI_TANH_MSE : EPI_MSE_ONLY, a, s));
+        else
+            HIP_TRY(launch_gemm16(p2, true, false, task.backward ? EPI_BIAS_STATS : EPI_STATS_ONLY, a, s));
         MARK(2);
 
         // row losses, and for a gradient dO = softmax(Z) - onehot in bf16 in place of the logits; loss (+)= sum
-        if (task.backward)
+        if (ts)
+            hipLaunchKernelGGL(mse16_finish_kernel, dim3((rows + 255) / 256), dim3(256), 0, s, rows,
+                               (const float2 *)stats, a.stat_groups, row_loss);
+        else if (task.backward)
             hipLaunchKernelGGL(softmax16_finish_kernel<true>, dim3((rows + 3) / 4), dim3(256), 0, s, dO, L.ldz, n_out,
                                rows, (const float2 *)stats, a.stat_groups, (const float *)zlab, ys, row_loss, row_lse);
         else
@@ -983,6 +996,37 @@ int ulsnn_sgemm(char transa, char transb, int m, int n, int k, float alpha, cons
     return launch_gemm(p, is_n(transa), is_t(transb), EPI_AXPBY, a, s) == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
 }
 
+int ulsnn_sgemm_ws(char transa, char transb, int m, int n, int k, float alpha, const float *A, int lda,
+                   const float *B, int ldb, float beta, float *C, int ldc, void *workspace, size_t workspace_bytes,
+                   void *hip_stream)
+{
+    if (!(is_n(transa) || is_t(transa)) || !(is_n(transb) || is_t(transb))) return ULSNN_ERR_TRANS;
+    if (m < 0 || n < 0 || k < 0) return ULSNN_ERR_DIM;
+    const int cols_a = is_n(transa) ? k : m;
+    const int cols_b = is_n(transb) ? n : k;
+    if (lda < std::max(1, cols_a) || ldb < std::max(1, cols_b) || ldc < std::max(1, n)) return ULSNN_ERR_LD;
+    if (lda > ULSNN_MAX_LD || ldb > ULSNN_MAX_LD) return ULSNN_ERR_UNSUPPORTED;
+    if (workspace_bytes > 0 && (!workspace || ((uintptr_t)workspace & 255) != 0)) return ULSNN_ERR_WORKSPACE;
+    if (m == 0 || n == 0 || k == 0 || alpha == 0.0f)
+        return ulsnn_sgemm(transa, transb, m, n, k, alpha, A, lda, B, ldb, beta, C, ldc, hip_stream);
+    if (!C || !A || !B) return ULSNN_ERR_NULL;
+    // as many k slices as the planner likes and the workspace can hold partial products for
+    const size_t slices = workspace_bytes / ((size_t)m * n * sizeof(float));
+    const GemmPlan p = plan_gemm(m, n, k, is_n(transa), is_t(transb), (int)std::min<size_t>(64, std::max<size_t>(1, slices)),
+                                 ALL_CFGS);
+    hipStream_t s = (hipStream_t)hip_stream;
+    GemmArgs a{};
+    a.A = A; a.B = B; a.C = C; a.M = m; a.N = n; a.K = k; a.lda = lda; a.ldb = ldb; a.ldc = ldc;
+    a.alpha = alpha; a.beta = beta;
+    if (p.splits == 1)
+        return launch_gemm(p, is_n(transa), is_t(transb), EPI_AXPBY, a, s) == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
+    GemmArgs q = a;
+    q.C = (float *)workspace;
+    q.partial_stride = (size_t)m * n;
+    if (launch_gemm(p, is_n(transa), is_t(transb), EPI_PARTIAL, q, s) != hipSuccess) return ULSNN_ERR_HIP;
+    return launch_reduce(p.splits, EPI_AXPBY, a, (const float *)workspace, s) == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
+}
+
 size_t ulsnn_mlp_grad_workspace_bytes(const ulsnn_mlp_desc *desc, int batch)
 {
     if (!desc_ok(desc) || batch < 0) return 0;
@@ -1061,7 +1105,6 @@ int ulsnn_mlp_grad_mse(const ulsnn_mlp_desc *desc, const void *W1, const void *W
 {
     const int rc = check_mlp_args(desc, W1, W2, X, T, batch, dW1, dW2, loss, true);
     if (rc != ULSNN_OK) return rc;
-    if (desc->operand_dtype != 0) return ULSNN_ERR_UNSUPPORTED;
     return mlp_grad_impl(desc, W1, W2, X, MlpTask{nullptr, T, true}, batch, dW1, dW2, loss, desc->accumulate != 0);
 }
 
@@ -1070,7 +1113,6 @@ int ulsnn_mlp_mse(const ulsnn_mlp_desc *desc, const void *W1, const void *W2, co
 {
     const int rc = check_mlp_args(desc, W1, W2, X, T, batch, nullptr, nullptr, loss, false);
     if (rc != ULSNN_OK) return rc;
-    if (desc->operand_dtype != 0) return ULSNN_ERR_UNSUPPORTED;
     return mlp_grad_impl(desc, W1, W2, X, MlpTask{nullptr, T, false}, batch, nullptr, nullptr, loss,
                          desc->accumulate != 0);
 }

@@ -177,8 +177,8 @@ def test_loss_only_and_mse_argument_errors():
     assert L.ulsnn_mlp_loss(C.byref(d), p, p, p, p, -1, p) == E_DIM
     assert L.ulsnn_mlp_loss(C.byref(d), p, p, p, p, 8, p) == E_WS            # needs the workspace
     assert L.ulsnn_mlp_grad_mse(C.byref(d), p, p, p, z, 8, p, p, p) == E_NULL   # targets missing
-    assert L.ulsnn_mlp_grad_mse(C.byref(_desc(operand_dtype=1)), p, p, p, p, 8, p, p, p) == E_UNSUP
-    assert L.ulsnn_mlp_mse(C.byref(_desc(operand_dtype=1)), p, p, p, p, 8, p) == E_UNSUP
+    assert L.ulsnn_mlp_grad_mse(C.byref(_desc(operand_dtype=1)), p, p, p, p, 8, p, p, p) == E_WS    # bf16: accepted
+    assert L.ulsnn_mlp_mse(C.byref(_desc(operand_dtype=2)), p, p, p, p, 8, p) == E_UNSUP
     assert L.ulsnn_mlp_grad_mse(C.byref(d), p, p, p, p, 8, p, p, p) == E_WS
 
 
@@ -243,6 +243,20 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0 and r.stdout.strip() == ""
     assert "ONE GPU" in r.stderr and "--gpus 2" in r.stderr
+
+
+def test_sgemm_ws_argument_errors():
+    L = ulsnn.load()
+    p = C.c_void_p(0x1000)
+    f = lambda ta, tb, m, n, k, lda, ldb, ldc, ws, wsb: L.ulsnn_sgemm_ws(ta, tb, m, n, k, 1.0, p, lda, p, ldb, 0.0, p, ldc,
+                                                                         ws, wsb, None)
+    assert f(b"X", b"N", 4, 4, 4, 4, 4, 4, None, 0) == E_TRANS
+    assert f(b"N", b"N", -1, 4, 4, 4, 4, 4, None, 0) == E_DIM
+    assert f(b"N", b"N", 4, 5, 6, 5, 5, 5, None, 0) == E_LD
+    assert f(b"N", b"N", 4, 5, 6, 6, 5, 5, None, 1024) == E_WS                   # bytes without a pointer
+    assert f(b"N", b"N", 4, 5, 6, 6, 5, 5, C.c_void_p(0x1010), 1024) == E_WS     # misaligned
+    assert f(b"N", b"N", 0, 5, 6, 6, 5, 5, None, 0) == OK                        # nothing to do
+    assert L.ulsnn_sgemm_ws(b"N", b"N", 4, 5, 6, 1.0, None, 6, p, 5, 0.0, p, 5, None, 0, None) == E_NULL
 
 
 def test_leading_dimension_and_network_size_limits():

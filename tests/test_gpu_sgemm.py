@@ -175,3 +175,37 @@ def test_every_tile_shape_on_ragged_edges(tile, ta, tb):
             got = dC.cpu().numpy()
             assert np.array_equal(got[:, :n], want[:, :n]), (ulsnn.TILE_SHAPES[tile], ta, tb, m, n, k, splits)
             assert np.isnan(got[:, n:]).all()
+
+
+@pytest.mark.parametrize("ta,tb,m,n,k", [("N", "N", 256, 256, 4096), ("T", "N", 400, 480, 3000), ("N", "T", 130, 70, 5001),
+                                          ("T", "T", 64, 48, 2048), ("N", "N", 1024, 1024, 1024)])
+def test_sgemm_with_workspace_splits_k_deterministically(ta, tb, m, n, k):
+    """ulsnn_sgemm_ws: the planner may cut k into slices when the workspace allows it (few tiles of C, long k).
+    Integer inputs (partial sums below 2^24): bit-exact against the oracle whatever the split; uniform inputs
+    inside the bound; the same call twice gives the same bits; without room for two slices it is ulsnn_sgemm."""
+    (ra, ca), (rb, cb) = _stored_dims(ta, tb, m, n, k)
+    ws = torch.empty(16 * m * n * 4, dtype=torch.uint8, device=DEV)
+    A = si.small_integers(7, si.T_A, ra, ca, bound=4).numpy()
+    B = si.small_integers(7, si.T_B, rb, cb, bound=4).numpy()
+    C0 = si.small_integers(7, si.T_C, m, n, even=True).numpy()
+    want = oracle.sgemm(ta, tb, m, n, k, 1.0, A, ca, B, cb, 0.5, C0, n)
+    dA, dB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    dC = torch.from_numpy(C0).to(DEV)
+    ulsnn.sgemm_ws(ta, tb, m, n, k, 1.0, dA, ca, dB, cb, 0.5, dC, n, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), want)
+    Au, Bu, Cu = si.gemm_operands(1, ra, ca, rb, cb, m, n)
+    ref, S = oracle.sgemm_exact(ta, tb, m, n, k, 1.0, Au.numpy(), ca, Bu.numpy(), cb, 0.5, Cu.numpy(), n)
+    runs = []
+    for workspace in (ws, ws, None):
+        dC = Cu.to(DEV)
+        ulsnn.sgemm_ws(ta, tb, m, n, k, 1.0, Au.to(DEV), ca, Bu.to(DEV), cb, 0.5, dC, n, workspace)
+        torch.cuda.synchronize()
+        runs.append(dC.cpu().numpy())
+        ratio = _check_bound(runs[-1], ref, S, 1.0, 0.5, Cu.numpy())
+        assert ratio < 5e-6
+    assert np.array_equal(runs[0], runs[1])
+    plain = Cu.to(DEV)
+    ulsnn.sgemm(ta, tb, m, n, k, 1.0, Au.to(DEV), ca, Bu.to(DEV), cb, 0.5, plain, n)
+    torch.cuda.synchronize()
+    assert np.array_equal(runs[2], plain.cpu().numpy())
