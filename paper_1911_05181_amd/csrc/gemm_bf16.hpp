@@ -18,6 +18,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "gemm.hpp"
 
 namespace ulsnn {
@@ -29,13 +31,21 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ float bf16_to_f32(u16 v) { return __uint_as_float((unsigned)v << 16); }
 
-// round to nearest, ties to even; NaN stays NaN
-__device__ __forceinline__ u16 f32_to_bf16(float x)
+// round to nearest, ties to even; NaN stays NaN: the conversion instruction of gfx950 (v_cvt_pk_bf16_f32)
+typedef float floatx2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u16 f32_to_bf16(float x) { return __builtin_bit_cast(u16, (__bf16)x); }
+__device__ __forceinline__ unsigned f32x2_to_bf16x2(float lo, float hi)
 {
-    unsigned u = __float_as_uint(x);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u16)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (u16)(u >> 16);
+    const floatx2_t v = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
+}
+typedef unsigned uintx4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u16x8 f32x8_to_bf16x8(const float (&v)[8])
+{
+    const uintx4_t p = {f32x2_to_bf16x2(v[0], v[1]), f32x2_to_bf16x2(v[2], v[3]), f32x2_to_bf16x2(v[4], v[5]),
+                        f32x2_to_bf16x2(v[6], v[7])};
+    return __builtin_bit_cast(u16x8, p);
 }
 
 struct Gemm16Args {
@@ -61,6 +71,12 @@ struct Gemm16Args {
     // the group's sum of (y - t)^2
     const float *targets;
     int ldt;
+    // DELTA_A kernels: A holds the bf16 LOGITS z[i][k]; the product uses the output delta exp(z - row_lse[i]) -
+    // [k == labels[i]] instead, formed in registers on the way from global memory to LDS (row_lse = +inf gives a
+    // zero row), and the workgroups of tile column 0 also write it, as bf16, to delta_out (same shape and row
+    // stride as A) for the products that follow.
+    const float *row_lse;
+    u16 *delta_out;
     int aligned;           // 1: A and B rows are 16-byte aligned (fast vector fetch allowed)
     int c_vec;             // 1: rows of C are 16-byte aligned (pointer and ldc): row-wise vector epilogue
     int aux_vec;           // 1: rows of aux are 16-byte aligned
@@ -330,9 +346,7 @@ __device__ __forceinline__ void gemm16_epilogue(const Gemm16Args &g, floatx16 (&
                     if (lab[pass] >= j && lab[pass] < j + 8 && lab[pass] < g.N) g.label_logit[i] = zl;
                     }
                     if (EPI == EPI_BIAS_STATS || EPI == EPI_TANH_MSE) {
-                        u16x8 o;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) o[e] = f32_to_bf16(v[e]);
+                        const u16x8 o = f32x8_to_bf16x8(v);
                         const size_t at = (size_t)i * g.ldc + j;
                         if (j + 7 < g.N) {
                             *reinterpret_cast<u16x8 *>(Ch + at) = o;
@@ -414,9 +428,7 @@ __device__ __forceinline__ void gemm16_epilogue(const Gemm16Args &g, floatx16 (&
                         for (int e = 0; e < 8; ++e) v[e] = tanh_f32(v[e]);
                     }
                     if (OUT_BF16) {
-                        u16x8 o;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) o[e] = f32_to_bf16(v[e]);
+                        const u16x8 o = f32x8_to_bf16x8(v);
                         if (whole) {
                             *reinterpret_cast<u16x8 *>(Ch + at) = o;
                         } else {
@@ -481,9 +493,10 @@ __device__ __forceinline__ void gemm16_epilogue(const Gemm16Args &g, floatx16 (&
 }
 
 // OUT_BF16: C is bf16 (EPI_BIAS_TANH, EPI_TANHGRAD, EPI_BIAS_STATS) else fp32.
-template <class Cfg, bool A_KC, bool B_KC, int EPI>
+template <class Cfg, bool A_KC, bool B_KC, int EPI, bool DELTA_A = false>
 __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, const int splits, u16 *lds)
 {
+    static_assert(!DELTA_A || A_KC, "the delta is formed on a k-contiguous A operand");
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = 32, THREADS = Cfg::THREADS;
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
     using PA = Panel16<A_KC, BM>;
@@ -538,7 +551,69 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
         for (int v = 0; v < NVB; ++v) rb[u][v] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
     }
 
+    // A panels are stored to LDS once per step, in step order, through store_a.  With DELTA_A it first turns the
+    // logits in the registers into the output delta (each thread's vectors stay on the same rows for the whole
+    // k loop, so the row's log-sum-exp and label are loaded once) and, in tile column 0, writes them out.
+    constexpr float LOG2E = 1.44269504088896340736f;
+    // Rows beyond the edge of the matrix repeat its last row (as the fetch does), so their stores rewrite that
+    // row's values and need no guard: the steady-state loop stays free of branches (a branch around a store makes
+    // the compiler wait for every outstanding load at the join).
+    static_assert(!DELTA_A || (BM * BK / 8) % THREADS == 0, "every thread owns whole vectors of the A panel");
+    float d_nl[NVA];       // -lse * log2(e) of the vector's row
+    int d_lab[NVA];        // label of that row, relative to the first k of the vector in the step about to be stored
+    unsigned d_off[NVA];   // offset of the vector in delta_out, from the tile's first row and the step's first k
+    u16 *d_out = nullptr;
+    if constexpr (DELTA_A) {
+#pragma unroll
+        for (int v = 0; v < NVA; ++v) {
+            const int f = tid + v * THREADS;
+            int row = f / 4;
+            row = row < g.M - i0 ? row : g.M - i0 - 1;
+            d_nl[v] = -g.row_lse[i0 + row] * LOG2E;
+            d_lab[v] = g.labels[i0 + row] - kbeg - (f % 4) * 8;
+            d_off[v] = (unsigned)row * (unsigned)g.lda + (unsigned)((f % 4) * 8);
+        }
+        d_out = g.delta_out + (size_t)i0 * g.lda + kbeg;
+    }
+    // write_tag: this workgroup also writes the delta out (tile column 0); a compile-time choice per copy of the loops
+    auto prepare_a = [&](auto write_tag, u16x8 (&reg)[NVA], const int k_first, const bool checked) {
+        constexpr bool WRITE = decltype(write_tag)::value;
+        if constexpr (DELTA_A) {
+#pragma unroll
+            for (int v = 0; v < NVA; ++v) {
+                const int f = tid + v * THREADS;
+                const int kq = k_first + (f % 4) * 8;          // global k of the vector's first element
+                const uintx4_t raw = __builtin_bit_cast(uintx4_t, reg[v]);
+                float d[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float x = __uint_as_float((e & 1) ? (raw[e >> 1] & 0xffff0000u) : (raw[e >> 1] << 16));
+                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(x, LOG2E, d_nl[v]));
+                    d[e] = p - (d_lab[v] == e ? 1.0f : 0.0f);
+                    if (checked && kq + e >= kend) d[e] = 0.f;
+                }
+                const u16x8 o = f32x8_to_bf16x8(d);
+                reg[v] = o;
+                d_lab[v] -= BK;
+                if constexpr (WRITE) {
+                    u16 *dst = d_out + (size_t)(k_first - kbeg) + d_off[v];
+                    if (!checked) {
+                        *reinterpret_cast<u16x8 *>(dst) = o;
+                    } else if (f / 4 < g.M - i0) {   // the checked fetch zero-fills rows beyond the edge: not copies
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (kq + e < kend) dst[e] = o[e];
+                    }
+                }
+            }
+        }
+    };
+    auto store_a = [&](u16 *stage_ptr, const u16x8 (&reg)[NVA]) {
+        panel16_store<A_KC, BM, THREADS, NVA>(stage_ptr, reg, tid);
+    };
+
     const u16 *na = pa, *nb = pb;   // where the next unchecked fetch reads
+    auto k_loops = [&](auto write_tag) {
     if (nkb > 0) {
         if (nfull > 0) {
 #pragma unroll
@@ -554,7 +629,8 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
             panel16_fetch_checked<A_KC, BM, THREADS, NVA>(ra[0], g.A, g.lda, i0, g.M, kbeg, kend, tid);
             panel16_fetch_checked<B_KC, BN, THREADS, NVB>(rb[0], g.B, g.ldb, j0, g.N, kbeg, kend, tid);
         }
-        panel16_store<A_KC, BM, THREADS, NVA>(stage_a(0), ra[0], tid);
+        prepare_a(write_tag, ra[0], kbeg, nfull == 0);
+        store_a(stage_a(0), ra[0]);
         panel16_store<B_KC, BN, THREADS, NVB>(stage_b(0), rb[0], tid);
     }
     __syncthreads();
@@ -591,8 +667,9 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
             fb.fetch(rb[u], nb, tid);
             na += step_a;
             nb += step_b;
+            prepare_a(write_tag, ra[un], kbeg + (base + u + 1) * BK, false);   // independent of the products below
             compute(cur);
-            panel16_store<A_KC, BM, THREADS, NVA>(stage_a(cur ^ 1), ra[un], tid);
+            store_a(stage_a(cur ^ 1), ra[un]);
             panel16_store<B_KC, BN, THREADS, NVB>(stage_b(cur ^ 1), rb[un], tid);
             __syncthreads();
         }
@@ -617,9 +694,10 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
                     panel16_fetch_checked<A_KC, BM, THREADS, NVA>(ra[un], g.A, g.lda, i0, g.M, k0, kend, tid);
                     panel16_fetch_checked<B_KC, BN, THREADS, NVB>(rb[un], g.B, g.ldb, j0, g.N, k0, kend, tid);
                 }
+                if (next < nkb) prepare_a(write_tag, ra[un], kbeg + next * BK, next == nfull);
                 compute(cur);
                 if (next < nkb) {
-                    panel16_store<A_KC, BM, THREADS, NVA>(stage_a(cur ^ 1), ra[un], tid);
+                    store_a(stage_a(cur ^ 1), ra[un]);
                     panel16_store<B_KC, BN, THREADS, NVB>(stage_b(cur ^ 1), rb[un], tid);
                 }
                 __syncthreads();
@@ -636,23 +714,27 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
             panel16_fetch_checked<A_KC, BM, THREADS, NVA>(ra[0], g.A, g.lda, i0, g.M, k0, kend, tid);
             panel16_fetch_checked<B_KC, BN, THREADS, NVB>(rb[0], g.B, g.ldb, j0, g.N, k0, kend, tid);
         }
+        if (more) prepare_a(write_tag, ra[0], kbeg + (kb + 1) * BK, true);
         compute(cur);
         if (more) {
-            panel16_store<A_KC, BM, THREADS, NVA>(stage_a(cur ^ 1), ra[0], tid);
+            store_a(stage_a(cur ^ 1), ra[0]);
             panel16_store<B_KC, BN, THREADS, NVB>(stage_b(cur ^ 1), rb[0], tid);
         }
         __syncthreads();
     }
+    };
+    if (DELTA_A && tile_n == 0) k_loops(std::true_type{});
+    else k_loops(std::false_type{});
     static_assert(gemm16_lds_elems<Cfg, A_KC, B_KC>() * 2 >= Cfg::WM * Cfg::WN * EPILOGUE_SCRATCH_FLOATS * 4,
                   "epilogue scratch fits in the panels' LDS");
     gemm16_epilogue<Cfg, EPI>(g, acc, reinterpret_cast<float *>(lds) + wave * EPILOGUE_SCRATCH_FLOATS, i0, j0, z, tile_n);
 }
 
-template <class Cfg, bool A_KC, bool B_KC, int EPI>
+template <class Cfg, bool A_KC, bool B_KC, int EPI, bool DELTA_A = false>
 __global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm16_kernel(const Gemm16Args g)
 {
     __shared__ __attribute__((aligned(16))) u16 lds[gemm16_lds_elems<Cfg, A_KC, B_KC>()];
-    gemm16_tile<Cfg, A_KC, B_KC, EPI>(g, blockIdx.y * gridDim.x + blockIdx.x, gridDim.y, lds);
+    gemm16_tile<Cfg, A_KC, B_KC, EPI, DELTA_A>(g, blockIdx.y * gridDim.x + blockIdx.x, gridDim.y, lds);
 }
 
 }  // namespace ulsnn

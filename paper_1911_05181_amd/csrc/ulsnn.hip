@@ -419,11 +419,11 @@ Gemm16Plan plan_gemm16(int m, int n, int k, bool a_kc, bool b_kc, bool allow_spl
     return best;
 }
 
-template <class Cfg, bool A_KC, bool B_KC, int EPI>
+template <class Cfg, bool A_KC, bool B_KC, int EPI, bool DELTA_A = false>
 hipError_t launch16_one(const Gemm16Args &a, int splits, hipStream_t s)
 {
     const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)splits);
-    hipLaunchKernelGGL((gemm16_kernel<Cfg, A_KC, B_KC, EPI>), grid, dim3(Cfg::THREADS), 0, s, a);
+    hipLaunchKernelGGL((gemm16_kernel<Cfg, A_KC, B_KC, EPI, DELTA_A>), grid, dim3(Cfg::THREADS), 0, s, a);
     return hipGetLastError();
 }
 
@@ -470,6 +470,12 @@ hipError_t launch_gemm16(const Gemm16Plan &p, bool a_kc, bool b_kc, int epi, Gem
             return epi == EPI_TANH_MSE ? launch16_one<Cfg, true, false, EPI_TANH_MSE>(a, p.splits, s)
                                        : launch16_one<Cfg, true, false, EPI_MSE_ONLY>(a, p.splits, s);
         }
+        if (a.delta_out) {   // hidden-delta product that forms the output delta from the logits while loading them
+            if (!(a_kc && b_kc) || !a.aligned || !a.row_lse || !a.labels || (epi != EPI_TANHGRAD && epi != EPI_PARTIAL))
+                return hipErrorInvalidValue;
+            return epi == EPI_TANHGRAD ? launch16_one<Cfg, true, true, EPI_TANHGRAD, true>(a, p.splits, s)
+                                       : launch16_one<Cfg, true, true, EPI_PARTIAL, true>(a, p.splits, s);
+        }
         if (epi == EPI_TANHGRAD && a_kc && b_kc) return launch16_one<Cfg, true, true, EPI_TANHGRAD>(a, p.splits, s);
         if (epi == EPI_PARTIAL && a_kc && b_kc) return launch16_one<Cfg, true, true, EPI_PARTIAL>(a, p.splits, s);
         if (epi == EPI_PARTIAL && !a_kc && !b_kc) return launch16_one<Cfg, false, false, EPI_PARTIAL>(a, p.splits, s);
@@ -492,7 +498,7 @@ struct MlpLayout {
     int ldw1p, ldw2p;               // bf16 path: row strides of the 16-byte aligned copies of W1 and W2
     size_t floats_pa, floats_pb;    // split-k partial regions: A (dW2, then dW1) and B (hidden delta)
     size_t off_h, off_z, off_da1, off_rowloss, off_pa, off_pb, bytes;
-    size_t off_do16, off_w1p, off_w2p, off_zlab, off_lse;   // bf16 path only
+    size_t off_do16, off_w1p, off_w2p, off_zlab, off_lse, off_z16;   // bf16 path only
 };
 
 struct SlabPlans {
@@ -555,6 +561,7 @@ MlpLayout mlp_layout(const ulsnn_mlp_desc *d, int batch)
         L.off_w2p = off;  off += round_up((size_t)d->n_hid * L.ldw2p * 2, 256);
         L.off_zlab = off; off += round_up((size_t)L.slab * 4, 256);
         L.off_lse = off;  off += round_up((size_t)L.slab * 4, 256);
+        L.off_z16 = off;  off += round_up((size_t)L.slab * L.ldz * 2, 256);
     }
     L.bytes = std::max(off, small_net_bytes(d, batch));
     return L;
@@ -824,7 +831,8 @@ int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const
     char *ws = (char *)d->workspace;
     u16 *H = (u16 *)(ws + L.off_h);
     float2 *stats = (float2 *)(ws + L.off_z);
-    u16 *dO = (u16 *)(ws + L.off_do16);          // the logits as bf16, then the output delta in their place
+    u16 *dO = (u16 *)(ws + L.off_do16);          // the output delta, bf16
+    u16 *Z16 = (u16 *)(ws + L.off_z16);          // softmax form: the logits, bf16
     float *zlab = (float *)(ws + L.off_zlab);
     float *row_lse = (float *)(ws + L.off_lse);
     u16 *dA1 = (u16 *)(ws + L.off_da1);
@@ -874,7 +882,7 @@ int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const
         // Z = H W2 + b2 rounded to bf16, with the softmax statistics of every row taken from the fp32 accumulators
         // in the product's epilogue (an error-only call writes the statistics alone)
         a = Gemm16Args{};
-        a.A = H; a.lda = L.ldh; a.B = W2; a.ldb = ldw2; a.C = dO; a.ldc = L.ldz;
+        a.A = H; a.lda = L.ldh; a.B = W2; a.ldb = ldw2; a.C = ts ? dO : Z16; a.ldc = L.ldz;
         a.M = rows; a.N = n_out; a.K = n_hid; a.alpha = 1.f; a.bias = d->b2;
         a.stats = stats; a.label_logit = zlab; a.labels = ys; a.targets = ts; a.ldt = n_out;
         const int sgw = stat_group_width(p2.cfg);
@@ -885,15 +893,12 @@ int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const
             HIP_TRY(launch_gemm16(p2, true, false, task.backward ? EPI_BIAS_STATS : EPI_STATS_ONLY, a, s));
         MARK(2);
 
-        // row losses, and for a gradient dO = softmax(Z) - onehot in bf16 in place of the logits; loss (+)= sum
+        // row losses (and, softmax form, each row's log-sum-exp for the delta); loss (+)= their sum
         if (ts)
             hipLaunchKernelGGL(mse16_finish_kernel, dim3((rows + 255) / 256), dim3(256), 0, s, rows,
                                (const float2 *)stats, a.stat_groups, row_loss);
-        else if (task.backward)
-            hipLaunchKernelGGL(softmax16_finish_kernel<true>, dim3((rows + 3) / 4), dim3(256), 0, s, dO, L.ldz, n_out,
-                               rows, (const float2 *)stats, a.stat_groups, (const float *)zlab, ys, row_loss, row_lse);
         else
-            hipLaunchKernelGGL(softmax16_finish_kernel<false>, dim3((rows + 3) / 4), dim3(256), 0, s, dO, L.ldz, n_out,
+            hipLaunchKernelGGL(softmax16_finish_kernel<false>, dim3((rows + 3) / 4), dim3(256), 0, s, Z16, L.ldz, n_out,
                                rows, (const float2 *)stats, a.stat_groups, (const float *)zlab, ys, row_loss, row_lse);
         hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, row_loss, (long long)rows, loss, beta);
         HIP_TRY(hipGetLastError());
@@ -903,10 +908,13 @@ int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const
             continue;
         }
 
-        // dA1 = (dO W2^T) * (1 - H*H), stored bf16
+        // dA1 = (dO W2^T) * (1 - H*H), stored bf16.  Softmax form: the product reads the LOGITS and forms
+        // dO = softmax - onehot on the way into LDS, writing it out for the dW2 product and the bias gradient
+        // (no pass of its own over the 2 x batch x n_out bytes of logits and delta)
         Gemm16Args a4{};
-        a4.A = dO; a4.lda = L.ldz; a4.B = W2; a4.ldb = ldw2; a4.C = dA1; a4.ldc = L.ldh;
+        a4.A = ts ? dO : Z16; a4.lda = L.ldz; a4.B = W2; a4.ldb = ldw2; a4.C = dA1; a4.ldc = L.ldh;
         a4.M = rows; a4.N = n_hid; a4.K = n_out; a4.alpha = 1.f; a4.aux = H; a4.ldaux = L.ldh;
+        if (!ts) { a4.row_lse = row_lse; a4.labels = ys; a4.delta_out = dO; }
         // dW2 (+)= H^T dO
         Gemm16Args a3{};
         a3.A = H; a3.lda = L.ldh; a3.B = dO; a3.ldb = L.ldz; a3.C = dW2; a3.ldc = n_out;
