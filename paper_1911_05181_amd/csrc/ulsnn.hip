@@ -371,7 +371,8 @@ using T16_64 = Tile16<64, 64, 2, 2, 8, 1>;      // 256 threads, 8 workgroups / C
 // bound by LDS reads).  Two workgroups per CU, so the epilogue's stores are poorly hidden: long-k products only.
 using T16_256 = Tile16<256, 128, 2, 2, 2, 2>;
 // 256 x 256 with eight wavefronts (sub-tile 64 x 128), one workgroup per CU: a third less operand traffic per
-// product again.  Measured on the hidden-delta product (both operands k-contiguous): 164 -> 140 us at 32768 patterns.
+// product again.  Measured on the hidden-delta product (both operands k-contiguous): 164 -> 140 us at 32768 patterns;
+// on the dW2 product (both m-contiguous) at 65536 patterns: backward products 645 -> 618 us.
 using T16_256x256 = Tile16<256, 256, 4, 2, 2, 2>;
 
 enum Cfg16Id { CFG16_128 = 0, CFG16_64, CFG16_256, CFG16_256x256, CFG16_COUNT };
@@ -399,7 +400,7 @@ Gemm16Plan plan_gemm16(int m, int n, int k, bool a_kc, bool b_kc, bool allow_spl
     for (int ci = 0; ci < CFG16_COUNT; ++ci) {
         const CfgInfo &c = CFG16_INFO[ci];
         if (ci == CFG16_256 && k < CFG16_256_MIN_K) continue;
-        if (ci == CFG16_256x256 && !(a_kc && b_kc && k >= CFG16_256_MIN_K)) continue;
+        if (ci == CFG16_256x256 && !(a_kc == b_kc && k >= CFG16_256_MIN_K)) continue;   // NT and TN long-k products
         int max_splits = allow_split ? std::max(1, std::min(64, k / (8 * c.bk))) : 1;
         if ((size_t)m * n > 0) max_splits = (int)std::min<size_t>(max_splits, std::max<size_t>(1, max_partial_floats / ((size_t)m * n)));
         for (int s = 1; s <= max_splits; ++s) {
