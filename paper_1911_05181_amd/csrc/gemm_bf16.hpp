@@ -61,10 +61,14 @@ struct Gemm16Args {
     int tiles_m, tiles_n;
     size_t partial_stride; // EPI_PARTIAL: elements between consecutive partial results
     // EPI_BIAS_STATS / EPI_STATS_ONLY: softmax statistics of the logits, from the fp32 values before rounding.
-    // stats[i * stat_groups + tile_n * WN + wn] = (max, sum of exp(z - max)) over the columns of row i that the
-    // wavefront column (tile_n, wn) covers; label_logit[i] = z[i][labels[i]] where the label is in range.
+    // stats[(tile_n * WN + wn) * stat_stride + i] = (max, sum of exp(z - max)) over the columns of row i that the
+    // wavefront column (tile_n, wn) covers; label_logit[i] = z[i][labels[i]] where the label is in range.  Group-major,
+    // so that the 16 rows a wavefront finishes together leave as one 128-byte store and the kernel that joins the
+    // groups reads consecutive rows with consecutive lanes (row-major, every 8-byte pair was a partial line write:
+    // the output layer at 65536 patterns wrote 543 MB where 447 MB are due).
     float2 *stats;
     int stat_groups;       // tiles_n * WN of the launch's tile shape
+    size_t stat_stride;    // pairs between consecutive groups (>= M)
     float *label_logit;
     const int32_t *labels;
     // EPI_TANH_MSE / EPI_MSE_ONLY: dense fp32 targets t[i][j] (row stride ldt, 4-byte aligned); stats[..].x receives
@@ -368,7 +372,7 @@ __device__ __forceinline__ void gemm16_epilogue(const Gemm16Args &g, floatx16 (&
                 }
                 const int i = i0 + wrow + x * 32 + pass * 16 + srow;
                 if ((lane & 3) == 0 && i < g.M && j0 + wcol < g.N)
-                    g.stats[(size_t)i * g.stat_groups + group] = MSE ? make_float2(rs[pass], 0.f) : make_float2(rm[pass], rs[pass]);
+                    g.stats[(size_t)group * g.stat_stride + i] = MSE ? make_float2(rs[pass], 0.f) : make_float2(rm[pass], rs[pass]);
             }
         }
         return;

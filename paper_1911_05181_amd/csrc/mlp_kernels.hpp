@@ -131,67 +131,61 @@ __global__ __launch_bounds__(THREADS) void softmax_ce_long_kernel(float *__restr
     }
 }
 
-// Output stage of the bf16-operand path, after an output-layer product that left the logits as bf16 (Z16, row
-// stride ldz, a multiple of 8 so that rows are 16-byte aligned) together with per-row statistics: for each of
-// `groups` column groups (max, sum of exp(z - max)) of the fp32 logits, and the fp32 logit of the label.
-// One wavefront per pattern, four patterns per workgroup:
-//     lse = ln sum_c exp(z_c) joined from the groups;  row_loss[r] = lse - z_label  (0 if the label is out of range)
+// Output stage of the bf16-operand path, after an output-layer product that left, for each of `groups` column
+// groups, (max, sum of exp(z - max)) of the fp32 logits of every row (stats[group * stat_stride + row]) and the
+// fp32 logit of the label.  A workgroup joins the groups of 64 patterns: wavefront q takes groups q, q+4, ... of
+// each (consecutive lanes read consecutive rows), the four partial pairs meet in LDS in the order q = 0..3:
+//     lse = ln sum_c exp(z_c);  row_loss[r] = lse - z_label  (0 if the label is out of range)
 //     row_lse[r] = lse (+inf for an ignored pattern: exp(z - inf) = 0 gives its zero delta)
-//     WRITE_DELTA: z_c <- bf16(exp(z_c - lse) - [c == label]) in place (zero row if ignored; padding columns zero)
-template <bool WRITE_DELTA>
-__global__ __launch_bounds__(256) void softmax16_finish_kernel(u16 *__restrict__ Z16, int ldz, int n, int rows,
-                                                               const float2 *__restrict__ stats, int groups,
+__global__ __launch_bounds__(256) void softmax16_finish_kernel(int n, int rows, const float2 *__restrict__ stats,
+                                                               size_t stat_stride, int groups,
                                                                const float *__restrict__ label_logit,
                                                                const int32_t *__restrict__ labels,
                                                                float *__restrict__ row_loss,
                                                                float *__restrict__ row_lse)
 {
-    const int lane = threadIdx.x & 63;
-    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (r >= rows) return;                       // whole wavefronts leave; no workgroup barrier below
+    __shared__ float2 part[4][64];
+    const int lr = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int r = blockIdx.x * 64 + lr;
+    float m = -INFINITY, s = 0.f;
+    if (r < rows) {
+#pragma unroll 4
+        for (int gI = q; gI < groups; gI += 4) {
+            const float2 p = stats[(size_t)gI * stat_stride + r];
+            softmax_merge(m, s, p.x, p.y);
+        }
+    }
+    part[q][lr] = make_float2(m, s);
+    __syncthreads();
+    if (q != 0 || r >= rows) return;
+#pragma unroll
+    for (int k = 1; k < 4; ++k) softmax_merge(m, s, part[k][lr].x, part[k][lr].y);
     const int y = labels[r];
     const bool labelled = (y >= 0 && y < n);
-    const float2 *st = stats + (size_t)r * groups;
-    float m = -INFINITY;
-    for (int gI = lane; gI < groups; gI += 64) m = fmaxf(m, st[gI].x);
-    m = wave_max(m);
-    float s = 0.f;
-    for (int gI = lane; gI < groups; gI += 64) {
-        const float2 p = st[gI];
-        s += p.x == m ? p.y : p.y * __expf(p.x - m);
-    }
-    s = wave_sum(s);
     const float lse = m + __logf(s);
-    if (lane == 0) {
-        row_loss[r] = labelled ? lse - label_logit[r] : 0.f;
-        if (row_lse) row_lse[r] = labelled ? lse : INFINITY;
-    }
-    if (!WRITE_DELTA) return;
-    u16 *z = Z16 + (size_t)r * ldz;
-    for (int c0 = lane * 8; c0 < ldz; c0 += 64 * 8) {
-        const u16x8 raw = *reinterpret_cast<const u16x8 *>(z + c0);
-        u16x8 out;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int c = c0 + e;
-            const float d = __expf(bf16_to_f32(raw[e]) - lse) - (c == y ? 1.0f : 0.0f);
-            out[e] = (labelled && c < n) ? f32_to_bf16(d) : (u16)0;
-        }
-        *reinterpret_cast<u16x8 *>(z + c0) = out;
-    }
+    row_loss[r] = labelled ? lse - label_logit[r] : 0.f;
+    if (row_lse) row_lse[r] = labelled ? lse : INFINITY;
 }
 
 // Squared-error form of the bf16-operand path: the output layer's epilogue left, per row and column group, the sum
-// of (y - t)^2 in stats[..].x.  row_loss[r] = their sum in group order, one thread per pattern.
-__global__ __launch_bounds__(256) void mse16_finish_kernel(int rows, const float2 *__restrict__ stats, int groups,
+// of (y - t)^2 in stats[group * stat_stride + row].x.  row_loss[r] = their sum, taken as above (wavefront q sums
+// groups q, q+4, ...; the four partial sums are added in the order q = 0..3).
+__global__ __launch_bounds__(256) void mse16_finish_kernel(int rows, const float2 *__restrict__ stats,
+                                                           size_t stat_stride, int groups,
                                                            float *__restrict__ row_loss)
 {
-    const int r = blockIdx.x * 256 + threadIdx.x;
-    if (r >= rows) return;
-    const float2 *st = stats + (size_t)r * groups;
+    __shared__ float part[4][64];
+    const int lr = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int r = blockIdx.x * 64 + lr;
     float s = 0.f;
-    for (int gI = 0; gI < groups; ++gI) s += st[gI].x;
-    row_loss[r] = s;
+    if (r < rows) {
+#pragma unroll 4
+        for (int gI = q; gI < groups; gI += 4) s += stats[(size_t)gI * stat_stride + r].x;
+    }
+    part[q][lr] = s;
+    __syncthreads();
+    if (q != 0 || r >= rows) return;
+    row_loss[r] = ((s + part[1][lr]) + part[2][lr]) + part[3][lr];
 }
 
 // Output stage of the paper's own form (tanh outputs, summed squared error against dense targets): one workgroup

@@ -458,14 +458,14 @@ hipError_t launch_gemm16(const Gemm16Plan &p, bool a_kc, bool b_kc, int epi, Gem
         if (epi == EPI_BIAS && a_kc && !b_kc) return launch16_one<Cfg, true, false, EPI_BIAS>(a, p.splits, s);
         if ((epi == EPI_BIAS_STATS || epi == EPI_STATS_ONLY) && a_kc && !b_kc) {
             // one statistics group per wavefront column; the logits' rows must be 16-byte aligned
-            if (a.stat_groups != (a.N + Cfg::WTN - 1) / Cfg::WTN || !a.stats || !a.label_logit || !a.labels ||
+            if (a.stat_groups != (a.N + Cfg::WTN - 1) / Cfg::WTN || a.stat_stride < (size_t)a.M || !a.stats || !a.label_logit || !a.labels ||
                 (epi == EPI_BIAS_STATS && !a.c_vec))
                 return hipErrorInvalidValue;
             return epi == EPI_BIAS_STATS ? launch16_one<Cfg, true, false, EPI_BIAS_STATS>(a, p.splits, s)
                                          : launch16_one<Cfg, true, false, EPI_STATS_ONLY>(a, p.splits, s);
         }
         if ((epi == EPI_TANH_MSE || epi == EPI_MSE_ONLY) && a_kc && !b_kc) {
-            if (a.stat_groups != (a.N + Cfg::WTN - 1) / Cfg::WTN || !a.stats || !a.targets || a.ldt < a.N ||
+            if (a.stat_groups != (a.N + Cfg::WTN - 1) / Cfg::WTN || a.stat_stride < (size_t)a.M || !a.stats || !a.targets || a.ldt < a.N ||
                 (epi == EPI_TANH_MSE && !a.c_vec))
                 return hipErrorInvalidValue;
             return epi == EPI_TANH_MSE ? launch16_one<Cfg, true, false, EPI_TANH_MSE>(a, p.splits, s)
@@ -888,6 +888,7 @@ int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const
         a.stats = stats; a.label_logit = zlab; a.labels = ys; a.targets = ts; a.ldt = n_out;
         const int sgw = stat_group_width(p2.cfg);
         a.stat_groups = (n_out + sgw - 1) / sgw;
+        a.stat_stride = (size_t)rows;
         if (ts)   // the paper's output stage (tanh, squared error, delta) entirely in the epilogue
             HIP_TRY(launch_gemm16(p2, true, false, task.backward ? EPI_TANH_MSE : EPI_MSE_ONLY, a, s));
         else
@@ -896,11 +897,12 @@ int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const
 
         // row losses (and, softmax form, each row's log-sum-exp for the delta); loss (+)= their sum
         if (ts)
-            hipLaunchKernelGGL(mse16_finish_kernel, dim3((rows + 255) / 256), dim3(256), 0, s, rows,
-                               (const float2 *)stats, a.stat_groups, row_loss);
+            hipLaunchKernelGGL(mse16_finish_kernel, dim3((rows + 63) / 64), dim3(256), 0, s, rows,
+                               (const float2 *)stats, a.stat_stride, a.stat_groups, row_loss);
         else
-            hipLaunchKernelGGL(softmax16_finish_kernel<false>, dim3((rows + 3) / 4), dim3(256), 0, s, Z16, L.ldz, n_out,
-                               rows, (const float2 *)stats, a.stat_groups, (const float *)zlab, ys, row_loss, row_lse);
+            hipLaunchKernelGGL(softmax16_finish_kernel, dim3((rows + 63) / 64), dim3(256), 0, s, n_out, rows,
+                               (const float2 *)stats, a.stat_stride, a.stat_groups, (const float *)zlab, ys, row_loss,
+                               row_lse);
         hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, row_loss, (long long)rows, loss, beta);
         HIP_TRY(hipGetLastError());
         MARK(3);
