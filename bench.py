@@ -36,12 +36,14 @@ FLOP_PER_CLK_PER_CU = 256          # fp32 matrix instructions
 # HBM bytes per launch of each stage's kernels (calibrated rocprofv3 counters) are read from this summary at run time:
 # its lines "bench_traffic: stage=<name> bytes_per_launch=<n>".
 TRAFFIC_PROFILE = os.path.join("profiles", "mlp_grad_b4096_hbm_traffic_pmc.md")
+TRAFFIC_PROFILE_BF16 = os.path.join("profiles", "mlp_grad_bf16_b65536_hbm_traffic_pmc.md")
+PEAK_HBM_GBS = 8000.0
 
 
-def pmc_traffic():
+def pmc_traffic(profile=TRAFFIC_PROFILE):
     out = {}
     try:
-        for line in open(os.path.join(ROOT, TRAFFIC_PROFILE)):
+        for line in open(os.path.join(ROOT, profile)):
             if line.startswith("bench_traffic:"):
                 f = dict(kv.split("=") for kv in line.split()[1:])
                 out[f["stage"]] = float(f["bytes_per_launch"])
@@ -357,6 +359,18 @@ def main():
     gflops = flops * args.steps / dt / 1e9
     loss = out.loss.item()
 
+    # the same call timed one by one with events on the launch stream (each call waits for the one before)
+    n_single = max(20, min(args.steps, 50))
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_single)]
+    for e0, e1 in evs:
+        e0.record()
+        ulsnn.mlp_grad(W1, W2, X, y, out=out, workspace=ws)
+        e1.record()
+    torch.cuda.synchronize()
+    singles = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    per_call = {"n": n_single, "median_ms": round(singles[n_single // 2], 4), "min_ms": round(singles[0], 4),
+                "max_ms": round(singles[-1], 4)}
+
     # shader clock while the step runs: a probe wavefront on a second stream reads the cycle counter and the wall
     # clock for 20 ms in the middle of a run of the same steps
     info = ulsnn.device_info()
@@ -411,6 +425,7 @@ def main():
                       "gflops": round(flops * args.steps / dt_cold / 1e9, 1),
                       "frac_of_fp32_mfma_peak": round(flops * args.steps / dt_cold / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4),
                       "note": "the same K steps timed straight after the W warm-up steps of the fresh process"},
+        "per_call_events": per_call,
         "device": device,
         "loss": loss, "stages": stages, "roofline": roofline,
     }
@@ -489,6 +504,17 @@ def main():
         r["x_of_fp32_mfma_peak"] = round(r["gflops"] / (PEAK_FP32_MFMA_TFLOPS * 1e3), 3)
         r["frac_of_bf16_mfma_peak"] = round(r["gflops"] / 2.5e6, 4)
         r["workload"] = "same net, X/W/H/dO/dA1 in bf16, fp32 accumulate, batch 65536"
+        # HBM side of this workload: every tensor the step cannot avoid moving, once each way as listed
+        n_i, n_h, n_o = shape.n_in, shape.n_hid, shape.n_out
+        alg = 65536 * (n_i + 4 * n_h + 4 * n_o) * 2 + 3 * 2 * (n_i * n_h + n_h * n_o) + 4 * (n_i * n_h + n_h * n_o)
+        gbs = alg / (r["ms"] * 1e-3) / 1e9
+        r["roofline_hbm"] = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                             "frac": round(gbs / PEAK_HBM_GBS, 4), "algorithmic_bytes": alg,
+                             "algorithmic_bytes_note": "X read; H, logits, delta, dA1 written once and read once (bf16); "
+                                                       "bf16 weights read by three products; fp32 gradients written",
+                             "traffic": pmc_traffic(TRAFFIC_PROFILE_BF16).get("bf16_gradient"),
+                             "traffic_unit": "bytes of HBM per gradient (calibrated PMC, all kernels)",
+                             "traffic_source": TRAFFIC_PROFILE_BF16}
         result["bf16"] = r
         # the squared-error form on the same operands (dense fp32 targets, 840 MB)
         Wb1, Wb2, Xbb = W1.to(torch.bfloat16), W2.to(torch.bfloat16), Xb.to(torch.bfloat16)
@@ -515,8 +541,26 @@ def main():
         result["sgemm"] = bench_sgemm(ulsnn, si, torch, args.sgemm_sizes)
         result["sgemm"].update(bench_sgemm_strided_and_cold(ulsnn, si, torch, args.sgemm_sizes))
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(si, shape, W1c, W2c, Xc, yc)
-        result["cpu_baselines"] = cpu_baselines_other(si, torch, shape, W1c, W2c)
+        cb = cpu_baseline(si, shape, W1c, W2c, Xc, yc)
+        cb["gpu_speedup"] = round(gflops / cb["value"], 1)
+        result["cpu_baseline"] = cb
+        others = cpu_baselines_other(si, torch, shape, W1c, W2c)
+        # the epoch workload: the 4096-pattern slice above, scaled by the pattern count
+        others["epoch"] = {"value": cb["value"], "unit": "GFLOP/s", "cores": cb["cores"], "kind": "oracle",
+                           "seconds_scaled": round(9_000_000 / cb["patterns_per_s"], 1),
+                           "sample": "the 4096-pattern slice of cpu_baseline, time scaled by 9,000,000 / 4096"}
+        if "epoch" in result:
+            others["epoch"]["gpu_speedup"] = round(others["epoch"]["seconds_scaled"] / result["epoch"]["seconds"], 1)
+        if "small_net" in result:
+            others["small_net"]["gpu_speedup"] = round(others["small_net"]["us_per_call"] / result["small_net"]["us_per_call"], 1)
+        if "bf16" in result:
+            others["bf16_inputs"]["gpu_speedup"] = round(result["bf16"]["gflops"] / others["bf16_inputs"]["value"], 1)
+        for key, v in others.items():
+            if key.startswith("sgemm_") and "sgemm" in result:
+                g = result["sgemm"].get(key[len("sgemm_"):])
+                if g:
+                    v["gpu_speedup"] = round(g["gflops"] / v["value"], 1)
+        result["cpu_baselines"] = others
     else:
         result["cpu_baseline"] = None
     print(json.dumps(result), flush=True)

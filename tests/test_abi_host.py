@@ -357,3 +357,20 @@ def test_binding_checks_every_tensor_before_calling_the_library(monkeypatch):
         with pytest.raises(ValueError):
             b.sgemm_planned(5, 1, *args)
     del real_lib
+
+
+def test_bench_reads_its_traffic_figures_from_the_committed_profiles():
+    """bench.py's roofline.traffic comes from lines of the profile summaries, not from constants in the script."""
+    import importlib.util
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_for_test", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    fp32 = bench.pmc_traffic()
+    for stage in ("backward_products", "output_layer", "hidden_layer", "dW1_product"):
+        assert fp32[stage] > 1e6
+    # the paired backward launch moves at least its algorithmic bytes (read dO twice, H, W2; write the partials)
+    assert fp32["backward_products"] >= 2 * 4096 * 3203 * 4 + 4096 * 480 * 4 + 480 * 3203 * 4
+    bf16 = bench.pmc_traffic(bench.TRAFFIC_PROFILE_BF16)
+    assert bf16["bf16_gradient"] >= 65536 * (400 + 4 * 480 + 4 * 3203) * 2

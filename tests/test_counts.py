@@ -51,3 +51,4 @@ def test_per_pattern_flops_and_sgemm():
     five = (oracle.sgemm_flops(b, n_h, n_i) + oracle.sgemm_flops(b, n_o, n_h) + oracle.sgemm_flops(n_h, n_o, b)
             + oracle.sgemm_flops(b, n_h, n_o) + oracle.sgemm_flops(n_i, n_h, b))
     assert five == oracle.grad_flops(b, n_i, n_h, n_o)
+
