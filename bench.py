@@ -175,6 +175,27 @@ def bench_sgemm_strided_and_cold(ulsnn, si, torch, sizes):
                                             "frac_of_peak": round(gf / (PEAK_FP32_MFMA_TFLOPS * 1e3), 4)}
         del A, B, C0
     del scrub
+    # with a workspace (ulsnn_sgemm_ws) the planner may cut k into slices where a product cannot fill the chip
+    for tag, (ta, tb, m, n, k) in (("NN_512", ("N", "N", 512, 512, 512)), ("TN_256x256x65536", ("T", "N", 256, 256, 65536))):
+        A, B, C0 = si.gemm_operands(1, *((m, k) if ta == "N" else (k, m)), *((k, n) if tb == "N" else (n, k)), m, n,
+                                    device="cuda:0")
+        lda, ldb = A.shape[1], B.shape[1]
+        ws = torch.empty(64 * m * n * 4, dtype=torch.uint8, device="cuda:0")
+        row = {"plan": ulsnn.sgemm_ws_describe_plan(ta, tb, m, n, k, ws.numel()).strip()}
+        for name, f in (("ms", lambda: ulsnn.sgemm(ta, tb, m, n, k, 1.0, A, lda, B, ldb, 0.5, C0, n)),
+                        ("ms_with_workspace", lambda: ulsnn.sgemm_ws(ta, tb, m, n, k, 1.0, A, lda, B, ldb, 0.5, C0, n, ws))):
+            settle(torch, f, 0.03)
+            reps = 50
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                f()
+            e1.record()
+            e1.synchronize()
+            row[name] = round(e0.elapsed_time(e1) / reps, 4)
+        row["gflops_with_workspace"] = round(ulsnn.sgemm_flops(m, n, k) / (row["ms_with_workspace"] * 1e-3) / 1e9, 1)
+        out[f"{tag}_split_k"] = row
+        del A, B, C0, ws
     return out
 
 

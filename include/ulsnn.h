@@ -316,6 +316,9 @@ int ulsnn_sgemm_planned(int tile_shape, int k_splits, char transa, char transb, 
  * (section 3.1's operation), one line in the format of the lines above.  Launches nothing.
  */
 int ulsnn_sgemm_describe_plan(char transa, char transb, int m, int n, int k, char *buf, size_t buf_bytes);
+/* The same for ulsnn_sgemm_ws with a workspace of `workspace_bytes` bytes (splits > 1: k is cut and reduced). */
+int ulsnn_sgemm_ws_describe_plan(char transa, char transb, int m, int n, int k, size_t workspace_bytes, char *buf,
+                                 size_t buf_bytes);
 
 /*
  * Measurement aids (what a roofline fraction "at the measured clock" needs; the paper times wall clock, section 3.4).

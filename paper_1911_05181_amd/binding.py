@@ -98,6 +98,8 @@ def load():
     L.ulsnn_sgemm_planned.restype = i
     L.ulsnn_sgemm_describe_plan.argtypes = [C.c_char, C.c_char, i, i, i, C.c_char_p, C.c_size_t]
     L.ulsnn_sgemm_describe_plan.restype = i
+    L.ulsnn_sgemm_ws_describe_plan.argtypes = [C.c_char, C.c_char, i, i, i, C.c_size_t, C.c_char_p, C.c_size_t]
+    L.ulsnn_sgemm_ws_describe_plan.restype = i
     L.ulsnn_mlp_grad_describe_plan.argtypes = [C.POINTER(_MlpDesc), i, C.c_char_p, C.c_size_t]
     L.ulsnn_mlp_grad_describe_plan.restype = i
     L.ulsnn_device_info.argtypes = [C.POINTER(i), C.POINTER(i), C.POINTER(i)]
@@ -368,6 +370,15 @@ def sgemm_describe_plan(transa: str, transb: str, m: int, n: int, k: int) -> str
     rc = load().ulsnn_sgemm_describe_plan(transa.encode(), transb.encode(), m, n, k, buf, len(buf))
     if rc:
         raise UlsnnError(rc, "ulsnn_sgemm_describe_plan")
+    return buf.value.decode()
+
+
+def sgemm_ws_describe_plan(transa: str, transb: str, m: int, n: int, k: int, workspace_bytes: int) -> str:
+    """Tile shape, grid and k split ulsnn_sgemm_ws would use with a workspace of that size (host only)."""
+    buf = C.create_string_buffer(256)
+    rc = load().ulsnn_sgemm_ws_describe_plan(transa.encode(), transb.encode(), m, n, k, workspace_bytes, buf, len(buf))
+    if rc:
+        raise UlsnnError(rc, "ulsnn_sgemm_ws_describe_plan")
     return buf.value.decode()
 
 

@@ -1007,6 +1007,19 @@ int ulsnn_sgemm(char transa, char transb, int m, int n, int k, float alpha, cons
     return launch_gemm(p, is_n(transa), is_t(transb), EPI_AXPBY, a, s) == hipSuccess ? ULSNN_OK : ULSNN_ERR_HIP;
 }
 
+// Plan of a product that may cut k into at most `slices` slices.  A split plan costs a second launch (the
+// reduction), and two launches back to back take at least 12.6 us, which the cost model prices a little low
+// (measured, split against unsplit: 256^3 13 against 10 us, 512^3 12.6 against 15.7, 1024^3 TN 33 against 27,
+// 2048^3 TN 158 against 168).  So a split plan is taken only where the model promises at least a fifth less time:
+// the products that cannot fill the chip without it (512^3, small outputs with a long k), not the close calls.
+GemmPlan plan_sgemm_ws(int m, int n, int k, bool a_kc, bool b_kc, size_t slices)
+{
+    const GemmPlan one = plan_gemm(m, n, k, a_kc, b_kc, 1, ALL_CFGS);
+    if (slices < 2) return one;
+    const GemmPlan cut = plan_gemm(m, n, k, a_kc, b_kc, (int)std::min<size_t>(64, slices), ALL_CFGS);
+    return (cut.splits > 1 && cut.est_us < 0.8 * one.est_us) ? cut : one;
+}
+
 int ulsnn_sgemm_ws(char transa, char transb, int m, int n, int k, float alpha, const float *A, int lda,
                    const float *B, int ldb, float beta, float *C, int ldc, void *workspace, size_t workspace_bytes,
                    void *hip_stream)
@@ -1023,8 +1036,7 @@ int ulsnn_sgemm_ws(char transa, char transb, int m, int n, int k, float alpha, c
     if (!C || !A || !B) return ULSNN_ERR_NULL;
     // as many k slices as the planner likes and the workspace can hold partial products for
     const size_t slices = workspace_bytes / ((size_t)m * n * sizeof(float));
-    const GemmPlan p = plan_gemm(m, n, k, is_n(transa), is_t(transb), (int)std::min<size_t>(64, std::max<size_t>(1, slices)),
-                                 ALL_CFGS);
+    const GemmPlan p = plan_sgemm_ws(m, n, k, is_n(transa), is_t(transb), slices);
     hipStream_t s = (hipStream_t)hip_stream;
     GemmArgs a{};
     a.A = A; a.B = B; a.C = C; a.M = m; a.N = n; a.K = k; a.lda = lda; a.ldb = ldb; a.ldc = ldc;
@@ -1423,6 +1435,20 @@ int ulsnn_sgemm_describe_plan(char transa, char transb, int m, int n, int k, cha
     const GemmPlan p = plan_gemm(m, n, k, is_n(transa), is_t(transb), 1, ALL_CFGS);
     snprintf(buf, buf_bytes, "tile=%s tiles=%dx%d splits=%d kchunk=%d model_us=%.1f\n", CFG_INFO[p.cfg].name,
              p.tiles_m, p.tiles_n, p.splits, p.kchunk, p.est_us);
+    return ULSNN_OK;
+}
+
+int ulsnn_sgemm_ws_describe_plan(char transa, char transb, int m, int n, int k, size_t workspace_bytes, char *buf,
+                                 size_t buf_bytes)
+{
+    if (!buf) return ULSNN_ERR_NULL;
+    if (!(is_n(transa) || is_t(transa)) || !(is_n(transb) || is_t(transb))) return ULSNN_ERR_TRANS;
+    if (m < 1 || n < 1 || k < 1 || buf_bytes < 1) return ULSNN_ERR_DIM;
+    const size_t slices = workspace_bytes / ((size_t)m * n * sizeof(float));
+    const GemmPlan p = plan_sgemm_ws(m, n, k, is_n(transa), is_t(transb), slices);
+    const GemmPlan cut = plan_gemm(m, n, k, is_n(transa), is_t(transb), (int)std::min<size_t>(64, std::max<size_t>(1, slices)), ALL_CFGS);
+    snprintf(buf, buf_bytes, "tile=%s tiles=%dx%d splits=%d kchunk=%d model_us=%.1f (best split plan: %d slices, %.1f us)\n",
+             CFG_INFO[p.cfg].name, p.tiles_m, p.tiles_n, p.splits, p.kchunk, p.est_us, cut.splits, cut.est_us);
     return ULSNN_OK;
 }
 

@@ -374,3 +374,23 @@ def test_bench_reads_its_traffic_figures_from_the_committed_profiles():
     assert fp32["backward_products"] >= 2 * 4096 * 3203 * 4 + 4096 * 480 * 4 + 480 * 3203 * 4
     bf16 = bench.pmc_traffic(bench.TRAFFIC_PROFILE_BF16)
     assert bf16["bf16_gradient"] >= 65536 * (400 + 4 * 480 + 4 * 3203) * 2
+
+
+def test_sgemm_ws_plan_splits_only_where_it_pays():
+    """Host only: with a workspace the planner cuts k where the product cannot fill the chip otherwise (512^3, a small
+    output with a long k) and leaves the close calls unsplit (256^3, 1024^3); without room for two slices never."""
+    def splits(*a):
+        return int(ulsnn.sgemm_ws_describe_plan(*a).split("splits=")[1].split()[0])
+    room = lambda m, n: 64 * m * n * 4
+    assert splits("N", "N", 512, 512, 512, room(512, 512)) > 1
+    assert splits("T", "N", 256, 256, 65536, room(256, 256)) > 8
+    assert splits("N", "N", 256, 256, 256, room(256, 256)) == 1
+    assert splits("N", "T", 1024, 1024, 1024, room(1024, 1024)) == 1
+    assert splits("N", "N", 512, 512, 512, 512 * 512 * 4) == 1
+    assert splits("N", "N", 512, 512, 512, 0) == 1
+    L = ulsnn.load()
+    import ctypes
+    buf = ctypes.create_string_buffer(64)
+    assert L.ulsnn_sgemm_ws_describe_plan(b"N", b"N", 8, 8, 8, 0, None, 8) == 1      # null buffer
+    assert L.ulsnn_sgemm_ws_describe_plan(b"X", b"N", 8, 8, 8, 0, buf, 64) == 2      # bad trans
+    assert L.ulsnn_sgemm_ws_describe_plan(b"N", b"N", 0, 8, 8, 0, buf, 64) == 3      # bad dimension

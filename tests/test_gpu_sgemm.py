@@ -185,6 +185,9 @@ def test_sgemm_with_workspace_splits_k_deterministically(ta, tb, m, n, k):
     inside the bound; the same call twice gives the same bits; without room for two slices it is ulsnn_sgemm."""
     (ra, ca), (rb, cb) = _stored_dims(ta, tb, m, n, k)
     ws = torch.empty(16 * m * n * 4, dtype=torch.uint8, device=DEV)
+    plan = ulsnn.sgemm_ws_describe_plan(ta, tb, m, n, k, ws.numel())
+    splits = int(plan.split("splits=")[1].split()[0])
+    assert (splits > 1) == (k > 1024), plan      # the long-k cases really take the split path, 1024^3 does not
     A = si.small_integers(7, si.T_A, ra, ca, bound=4).numpy()
     B = si.small_integers(7, si.T_B, rb, cb, bound=4).numpy()
     C0 = si.small_integers(7, si.T_C, m, n, even=True).numpy()
