@@ -87,7 +87,8 @@ int ulsnn_sgemm_ws(char transa, char transb, int m, int n, int k, float alpha, c
  *   operand_dtype: 0 = fp32 storage of W1, W2, X (the paper's precision; section 4.2 reports 32 bits to be enough).
  *                  1 = bf16 storage (section 4.2 notes that 16 bits can suffice for small nets): W1, W2 and X point
  *                      at bf16 values (upper 16 bits of an IEEE float, row-major, dense); H, the logits, dO and dA1
- *                      are kept in bf16 (round to nearest even) and multiplied on the bf16 matrix instructions; every
+ *                      are bf16 as well (round to nearest even; dO is formed from the rounded logits inside the
+ *                      products that use it) and multiplied on the bf16 matrix instructions; every
  *                      product accumulates in fp32; the softmax statistics (row maximum, sum of exponentials, the
  *                      label's logit) and with them the loss are taken from the fp32 accumulators of the output
  *                      layer before its logits are rounded; dW1, dW2, db1, db2 (and b1, b2) stay fp32.

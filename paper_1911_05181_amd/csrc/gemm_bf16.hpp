@@ -75,12 +75,12 @@ struct Gemm16Args {
     // the group's sum of (y - t)^2
     const float *targets;
     int ldt;
-    // DELTA_A kernels: A holds the bf16 LOGITS z[i][k]; the product uses the output delta exp(z - row_lse[i]) -
-    // [k == labels[i]] instead, formed in registers on the way from global memory to LDS (row_lse = +inf gives a
-    // zero row), and the workgroups of tile column 0 also write it, as bf16, to delta_out (same shape and row
-    // stride as A) for the products that follow.
+    // DELTA kernels: one operand holds the bf16 LOGITS z[pattern][class] and the product uses the output delta
+    //     exp(z - row_lse[pattern]) - [class == labels[pattern]]   (rounded to bf16)
+    // instead, formed in registers on the way from global memory to LDS; row_lse = +inf gives a zero row.  DELTA 1:
+    // the operand is A of an NT product (patterns = rows of A, classes = k: the hidden delta); DELTA 2: it is B of a TN
+    // product (patterns = k, classes = columns of B: the dW2 product).  The delta itself is never stored.
     const float *row_lse;
-    u16 *delta_out;
     int aligned;           // 1: A and B rows are 16-byte aligned (fast vector fetch allowed)
     int c_vec;             // 1: rows of C are 16-byte aligned (pointer and ldc): row-wise vector epilogue
     int aux_vec;           // 1: rows of aux are 16-byte aligned
@@ -497,10 +497,12 @@ __device__ __forceinline__ void gemm16_epilogue(const Gemm16Args &g, floatx16 (&
 }
 
 // OUT_BF16: C is bf16 (EPI_BIAS_TANH, EPI_TANHGRAD, EPI_BIAS_STATS) else fp32.
-template <class Cfg, bool A_KC, bool B_KC, int EPI, bool DELTA_A = false>
+template <class Cfg, bool A_KC, bool B_KC, int EPI, int DELTA = 0>
 __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, const int splits, u16 *lds)
 {
-    static_assert(!DELTA_A || A_KC, "the delta is formed on a k-contiguous A operand");
+    constexpr bool DELTA_A = DELTA == 1, DELTA_B = DELTA == 2;
+    static_assert(!DELTA_A || A_KC, "the delta is formed on a k-contiguous A operand ...");
+    static_assert(!DELTA_B || !B_KC, "... or on an m-contiguous B operand");
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = 32, THREADS = Cfg::THREADS;
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
     using PA = Panel16<A_KC, BM>;
@@ -555,60 +557,80 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
         for (int v = 0; v < NVB; ++v) rb[u][v] = u16x8{0, 0, 0, 0, 0, 0, 0, 0};
     }
 
-    // A panels are stored to LDS once per step, in step order, through store_a.  With DELTA_A it first turns the
-    // logits in the registers into the output delta (each thread's vectors stay on the same rows for the whole
-    // k loop, so the row's log-sum-exp and label are loaded once) and, in tile column 0, writes them out.
+    // DELTA: the logits in the fetch registers become the output delta just before they are stored to LDS (the
+    // transform is issued ahead of the matrix instructions of the step that hides it).
     constexpr float LOG2E = 1.44269504088896340736f;
-    // Rows beyond the edge of the matrix repeat its last row (as the fetch does), so their stores rewrite that
-    // row's values and need no guard: the steady-state loop stays free of branches (a branch around a store makes
-    // the compiler wait for every outstanding load at the join).
+    auto to_delta = [&](u16x8 &reg, const float nl, const int lab) {   // nl = -lse*log2(e); lab relative to element 0
+        const uintx4_t raw = __builtin_bit_cast(uintx4_t, reg);
+        float d[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float x = __uint_as_float((e & 1) ? (raw[e >> 1] & 0xffff0000u) : (raw[e >> 1] << 16));
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(x, LOG2E, nl));
+            d[e] = p - (lab == e ? 1.0f : 0.0f);
+        }
+        reg = f32x8_to_bf16x8(d);
+    };
+    // DELTA 1 (A, k-contiguous): each thread's vectors stay on the same rows (patterns) for the whole k loop, so the
+    // row's log-sum-exp and label are loaded once; the label moves BK classes down per step.
     static_assert(!DELTA_A || (BM * BK / 8) % THREADS == 0, "every thread owns whole vectors of the A panel");
-    float d_nl[NVA];       // -lse * log2(e) of the vector's row
-    int d_lab[NVA];        // label of that row, relative to the first k of the vector in the step about to be stored
-    unsigned d_off[NVA];   // offset of the vector in delta_out, from the tile's first row and the step's first k
-    u16 *d_out = nullptr;
+    float a_nl[NVA];       // -lse * log2(e) of the vector's row
+    int a_lab[NVA];        // label of that row, relative to the first k of the vector in the step about to be stored
     if constexpr (DELTA_A) {
 #pragma unroll
         for (int v = 0; v < NVA; ++v) {
             const int f = tid + v * THREADS;
             int row = f / 4;
             row = row < g.M - i0 ? row : g.M - i0 - 1;
-            d_nl[v] = -g.row_lse[i0 + row] * LOG2E;
-            d_lab[v] = g.labels[i0 + row] - kbeg - (f % 4) * 8;
-            d_off[v] = (unsigned)row * (unsigned)g.lda + (unsigned)((f % 4) * 8);
+            a_nl[v] = -g.row_lse[i0 + row] * LOG2E;
+            a_lab[v] = g.labels[i0 + row] - kbeg - (f % 4) * 8;
         }
-        d_out = g.delta_out + (size_t)i0 * g.lda + kbeg;
     }
-    // write_tag: this workgroup also writes the delta out (tile column 0); a compile-time choice per copy of the loops
-    auto prepare_a = [&](auto write_tag, u16x8 (&reg)[NVA], const int k_first, const bool checked) {
-        constexpr bool WRITE = decltype(write_tag)::value;
+    auto prepare_a = [&](u16x8 (&reg)[NVA], const int k_first, const bool checked) {
         if constexpr (DELTA_A) {
 #pragma unroll
             for (int v = 0; v < NVA; ++v) {
-                const int f = tid + v * THREADS;
-                const int kq = k_first + (f % 4) * 8;          // global k of the vector's first element
-                const uintx4_t raw = __builtin_bit_cast(uintx4_t, reg[v]);
-                float d[8];
+                to_delta(reg[v], a_nl[v], a_lab[v]);
+                a_lab[v] -= BK;
+                if (checked) {                                 // the partial last step: classes beyond K stay zero
+                    const int kq = k_first + ((tid + v * THREADS) % 4) * 8;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float x = __uint_as_float((e & 1) ? (raw[e >> 1] & 0xffff0000u) : (raw[e >> 1] << 16));
-                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(x, LOG2E, d_nl[v]));
-                    d[e] = p - (d_lab[v] == e ? 1.0f : 0.0f);
-                    if (checked && kq + e >= kend) d[e] = 0.f;
+                    for (int e = 0; e < 8; ++e)
+                        if (kq + e >= kend) reg[v][e] = 0;
                 }
-                const u16x8 o = f32x8_to_bf16x8(d);
-                reg[v] = o;
-                d_lab[v] -= BK;
-                if constexpr (WRITE) {
-                    u16 *dst = d_out + (size_t)(k_first - kbeg) + d_off[v];
-                    if (!checked) {
-                        *reinterpret_cast<u16x8 *>(dst) = o;
-                    } else if (f / 4 < g.M - i0) {   // the checked fetch zero-fills rows beyond the edge: not copies
+            }
+        }
+    };
+    // DELTA 2 (B, m-contiguous): a vector is eight classes of ONE pattern, and the pattern (the k row) changes with
+    // every step, so log-sum-exp and label of a vector's pattern travel with the panel: they are loaded when the
+    // panel is fetched, into the same register slot.  A k row beyond the range (partial last step, zero filled)
+    // gets -inf, which keeps it zero.
+    static_assert(!DELTA_B || (BN * BK / 8) % THREADS == 0, "every thread owns whole vectors of the B panel");
+    // (The loaded values are kept raw until the panel is stored: arithmetic on them at fetch time would make the
+    // compiler wait for the loads on the spot.)
+    float b_lse[Cfg::PREFETCH][NVB];
+    int b_lab[Cfg::PREFETCH][NVB];
+    auto fetch_b_meta = [&](const int slot, const int k_first, const bool checked) {
+        if constexpr (DELTA_B) {
 #pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (kq + e < kend) dst[e] = o[e];
-                    }
+            for (int v = 0; v < NVB; ++v) {
+                const int k = k_first + (tid + v * THREADS) / (BN / 8);
+                if (!checked || k < kend) {
+                    b_lse[slot][v] = g.row_lse[k];
+                    b_lab[slot][v] = g.labels[k];
+                } else {
+                    b_lse[slot][v] = INFINITY;
+                    b_lab[slot][v] = -8;
                 }
+            }
+        }
+    };
+    auto prepare_b = [&](const int slot, u16x8 (&reg)[NVB]) {
+        if constexpr (DELTA_B) {
+#pragma unroll
+            for (int v = 0; v < NVB; ++v) {
+                const int col0 = j0 + ((tid + v * THREADS) % (BN / 8)) * 8;     // class of the vector's first element
+                to_delta(reg[v], -b_lse[slot][v] * LOG2E, b_lab[slot][v] - col0);
             }
         }
     };
@@ -616,24 +638,31 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
         panel16_store<A_KC, BM, THREADS, NVA>(stage_ptr, reg, tid);
     };
 
-    const u16 *na = pa, *nb = pb;   // where the next unchecked fetch reads
-    auto k_loops = [&](auto write_tag) {
+    const u16 *na = pa, *nb = pb;   // where the next unchecked fetch reads ...
+    int nk = kbeg;                  // ... and the k it starts at
+    auto fetch_full = [&](const int slot) {
+        fa.fetch(ra[slot], na, tid);
+        fb.fetch(rb[slot], nb, tid);
+        fetch_b_meta(slot, nk, false);
+        na += step_a;
+        nb += step_b;
+        nk += BK;
+    };
+    auto fetch_checked = [&](const int slot, const int k0) {
+        panel16_fetch_checked<A_KC, BM, THREADS, NVA>(ra[slot], g.A, g.lda, i0, g.M, k0, kend, tid);
+        panel16_fetch_checked<B_KC, BN, THREADS, NVB>(rb[slot], g.B, g.ldb, j0, g.N, k0, kend, tid);
+        fetch_b_meta(slot, k0, true);
+    };
     if (nkb > 0) {
         if (nfull > 0) {
 #pragma unroll
-            for (int u = 0; u < D; ++u) {
-                if (u < nfull) {
-                    fa.fetch(ra[u], na, tid);
-                    fb.fetch(rb[u], nb, tid);
-                    na += step_a;
-                    nb += step_b;
-                }
-            }
+            for (int u = 0; u < D; ++u)
+                if (u < nfull) fetch_full(u);
         } else {
-            panel16_fetch_checked<A_KC, BM, THREADS, NVA>(ra[0], g.A, g.lda, i0, g.M, kbeg, kend, tid);
-            panel16_fetch_checked<B_KC, BN, THREADS, NVB>(rb[0], g.B, g.ldb, j0, g.N, kbeg, kend, tid);
+            fetch_checked(0, kbeg);
         }
-        prepare_a(write_tag, ra[0], kbeg, nfull == 0);
+        prepare_a(ra[0], kbeg, nfull == 0);
+        prepare_b(0, rb[0]);
         store_a(stage_a(0), ra[0]);
         panel16_store<B_KC, BN, THREADS, NVB>(stage_b(0), rb[0], tid);
     }
@@ -667,14 +696,25 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
         for (int u = 0; u < D; ++u) {
             const int cur = (base + u) & 1;
             const int un = (u + 1) % D;
-            fa.fetch(ra[u], na, tid);
-            fb.fetch(rb[u], nb, tid);
-            na += step_a;
-            nb += step_b;
-            prepare_a(write_tag, ra[un], kbeg + (base + u + 1) * BK, false);   // independent of the products below
+            fetch_full(u);
+            prepare_a(ra[un], kbeg + (base + u + 1) * BK, false);   // independent of the products below
+            prepare_b(un, rb[un]);
             compute(cur);
             store_a(stage_a(cur ^ 1), ra[un]);
             panel16_store<B_KC, BN, THREADS, NVB>(stage_b(cur ^ 1), rb[un], tid);
+            if constexpr (DELTA_B) {
+                // The dW2 product has the least idle time of all: left to itself the compiler puts the transform in
+                // one block ahead of the matrix instructions, and with every wavefront of the workgroup in step
+                // (a barrier per k step) the two kinds of work then take turns instead of overlapping.  Ask for one
+                // matrix instruction followed by the vector instructions that fit in its shadow (5 plain + 1
+                // transcendental; 3, 4 and 6 measured slower, and on the hidden-delta product any such order was).
+#pragma unroll
+                for (int i = 0; i < 2 * TM * TN; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 matrix instruction
+                    __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);   // 5 vector ALU instructions
+                    __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);   // 1 transcendental
+                }
+            }
             __syncthreads();
         }
     }
@@ -687,18 +727,13 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
             if (kb < nfull) {
                 const int cur = kb & 1, next = kb + 1;
                 const int un = (u + 1) % D;            // slot of step kb + 1
-                if (kb + D < nfull) {                  // refill the free slot with step kb + D
-                    fa.fetch(ra[u], na, tid);
-                    fb.fetch(rb[u], nb, tid);
-                    na += step_a;
-                    nb += step_b;
+                if (kb + D < nfull) fetch_full(u);     // refill the free slot with step kb + D
+                if (next == nfull && next < nkb)       // the partial last step: checked fetch, zero filled
+                    fetch_checked(un, kbeg + next * BK);
+                if (next < nkb) {
+                    prepare_a(ra[un], kbeg + next * BK, next == nfull);
+                    prepare_b(un, rb[un]);
                 }
-                if (next == nfull && next < nkb) {     // the partial last step: checked fetch, zero filled
-                    const int k0 = kbeg + next * BK;
-                    panel16_fetch_checked<A_KC, BM, THREADS, NVA>(ra[un], g.A, g.lda, i0, g.M, k0, kend, tid);
-                    panel16_fetch_checked<B_KC, BN, THREADS, NVB>(rb[un], g.B, g.ldb, j0, g.N, k0, kend, tid);
-                }
-                if (next < nkb) prepare_a(write_tag, ra[un], kbeg + next * BK, next == nfull);
                 compute(cur);
                 if (next < nkb) {
                     store_a(stage_a(cur ^ 1), ra[un]);
@@ -714,11 +749,10 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
         const int cur = kb & 1;
         const bool more = kb + 1 < nkb;
         if (more) {
-            const int k0 = kbeg + (kb + 1) * BK;
-            panel16_fetch_checked<A_KC, BM, THREADS, NVA>(ra[0], g.A, g.lda, i0, g.M, k0, kend, tid);
-            panel16_fetch_checked<B_KC, BN, THREADS, NVB>(rb[0], g.B, g.ldb, j0, g.N, k0, kend, tid);
+            fetch_checked(0, kbeg + (kb + 1) * BK);
+            prepare_a(ra[0], kbeg + (kb + 1) * BK, true);
+            prepare_b(0, rb[0]);
         }
-        if (more) prepare_a(write_tag, ra[0], kbeg + (kb + 1) * BK, true);
         compute(cur);
         if (more) {
             store_a(stage_a(cur ^ 1), ra[0]);
@@ -726,19 +760,16 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
         }
         __syncthreads();
     }
-    };
-    if (DELTA_A && tile_n == 0) k_loops(std::true_type{});
-    else k_loops(std::false_type{});
     static_assert(gemm16_lds_elems<Cfg, A_KC, B_KC>() * 2 >= Cfg::WM * Cfg::WN * EPILOGUE_SCRATCH_FLOATS * 4,
                   "epilogue scratch fits in the panels' LDS");
     gemm16_epilogue<Cfg, EPI>(g, acc, reinterpret_cast<float *>(lds) + wave * EPILOGUE_SCRATCH_FLOATS, i0, j0, z, tile_n);
 }
 
-template <class Cfg, bool A_KC, bool B_KC, int EPI, bool DELTA_A = false>
+template <class Cfg, bool A_KC, bool B_KC, int EPI, int DELTA = 0>
 __global__ __launch_bounds__(Cfg::THREADS, Cfg::WAVES_PER_SIMD) void gemm16_kernel(const Gemm16Args g)
 {
     __shared__ __attribute__((aligned(16))) u16 lds[gemm16_lds_elems<Cfg, A_KC, B_KC>()];
-    gemm16_tile<Cfg, A_KC, B_KC, EPI, DELTA_A>(g, blockIdx.y * gridDim.x + blockIdx.x, gridDim.y, lds);
+    gemm16_tile<Cfg, A_KC, B_KC, EPI, DELTA>(g, blockIdx.y * gridDim.x + blockIdx.x, gridDim.y, lds);
 }
 
 }  // namespace ulsnn

@@ -277,6 +277,28 @@ __global__ __launch_bounds__(256) void column_sum16_kernel(const u16 *__restrict
     }
 }
 
+// The same sum over the output delta of the softmax form, which the bf16-operand path never stores: D[r][c] =
+// exp(z[r][c] - row_lse[r]) - [c == labels[r]] from the bf16 logits Z (row_lse = +inf: an ignored pattern, zero row).
+__global__ __launch_bounds__(256) void column_sum16_delta_kernel(const u16 *__restrict__ Z, int ld, int R, int N,
+                                                                 const float *__restrict__ row_lse,
+                                                                 const int32_t *__restrict__ labels,
+                                                                 float *__restrict__ out, float beta)
+{
+    __shared__ float red[4][64];
+    const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int phase = threadIdx.x >> 6;
+    float s = 0.f;
+    if (c < N)
+        for (int r = phase; r < R; r += 4)
+            s += __expf(bf16_to_f32(Z[(size_t)r * ld + c]) - row_lse[r]) - (labels[r] == c ? 1.0f : 0.0f);
+    red[phase][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (phase == 0 && c < N) {
+        const float t = ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
+        out[c] = (beta != 0.f ? beta * out[c] : 0.f) + t;
+    }
+}
+
 // out[c] = beta*out[c] + sum_r D[r][c] for an R x N matrix: 64 columns per workgroup, 4 row phases.
 __global__ __launch_bounds__(256) void column_sum_kernel(const float *__restrict__ D, int ld, int R, int N,
                                                          float *__restrict__ out, float beta)

@@ -420,11 +420,11 @@ Gemm16Plan plan_gemm16(int m, int n, int k, bool a_kc, bool b_kc, bool allow_spl
     return best;
 }
 
-template <class Cfg, bool A_KC, bool B_KC, int EPI, bool DELTA_A = false>
+template <class Cfg, bool A_KC, bool B_KC, int EPI, int DELTA = 0>
 hipError_t launch16_one(const Gemm16Args &a, int splits, hipStream_t s)
 {
     const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)splits);
-    hipLaunchKernelGGL((gemm16_kernel<Cfg, A_KC, B_KC, EPI, DELTA_A>), grid, dim3(Cfg::THREADS), 0, s, a);
+    hipLaunchKernelGGL((gemm16_kernel<Cfg, A_KC, B_KC, EPI, DELTA>), grid, dim3(Cfg::THREADS), 0, s, a);
     return hipGetLastError();
 }
 
@@ -471,11 +471,13 @@ hipError_t launch_gemm16(const Gemm16Plan &p, bool a_kc, bool b_kc, int epi, Gem
             return epi == EPI_TANH_MSE ? launch16_one<Cfg, true, false, EPI_TANH_MSE>(a, p.splits, s)
                                        : launch16_one<Cfg, true, false, EPI_MSE_ONLY>(a, p.splits, s);
         }
-        if (a.delta_out) {   // hidden-delta product that forms the output delta from the logits while loading them
-            if (!(a_kc && b_kc) || !a.aligned || !a.row_lse || !a.labels || (epi != EPI_TANHGRAD && epi != EPI_PARTIAL))
-                return hipErrorInvalidValue;
-            return epi == EPI_TANHGRAD ? launch16_one<Cfg, true, true, EPI_TANHGRAD, true>(a, p.splits, s)
-                                       : launch16_one<Cfg, true, true, EPI_PARTIAL, true>(a, p.splits, s);
+        if (a.row_lse) {   // a product that forms the output delta from the logits while loading them
+            if (!a.aligned || !a.labels) return hipErrorInvalidValue;
+            if (a_kc && b_kc && epi == EPI_TANHGRAD) return launch16_one<Cfg, true, true, EPI_TANHGRAD, 1>(a, p.splits, s);
+            if (a_kc && b_kc && epi == EPI_PARTIAL) return launch16_one<Cfg, true, true, EPI_PARTIAL, 1>(a, p.splits, s);
+            if (!a_kc && !b_kc && epi == EPI_PARTIAL) return launch16_one<Cfg, false, false, EPI_PARTIAL, 2>(a, p.splits, s);
+            if (!a_kc && !b_kc && epi == EPI_AXPBY) return launch16_one<Cfg, false, false, EPI_AXPBY, 2>(a, p.splits, s);
+            return hipErrorInvalidValue;
         }
         if (epi == EPI_TANHGRAD && a_kc && b_kc) return launch16_one<Cfg, true, true, EPI_TANHGRAD>(a, p.splits, s);
         if (epi == EPI_PARTIAL && a_kc && b_kc) return launch16_one<Cfg, true, true, EPI_PARTIAL>(a, p.splits, s);
@@ -499,7 +501,7 @@ struct MlpLayout {
     int ldw1p, ldw2p;               // bf16 path: row strides of the 16-byte aligned copies of W1 and W2
     size_t floats_pa, floats_pb;    // split-k partial regions: A (dW2, then dW1) and B (hidden delta)
     size_t off_h, off_z, off_da1, off_rowloss, off_pa, off_pb, bytes;
-    size_t off_do16, off_w1p, off_w2p, off_zlab, off_lse, off_z16;   // bf16 path only
+    size_t off_do16, off_w1p, off_w2p, off_zlab, off_lse;   // bf16 path only
 };
 
 struct SlabPlans {
@@ -562,7 +564,6 @@ MlpLayout mlp_layout(const ulsnn_mlp_desc *d, int batch)
         L.off_w2p = off;  off += round_up((size_t)d->n_hid * L.ldw2p * 2, 256);
         L.off_zlab = off; off += round_up((size_t)L.slab * 4, 256);
         L.off_lse = off;  off += round_up((size_t)L.slab * 4, 256);
-        L.off_z16 = off;  off += round_up((size_t)L.slab * L.ldz * 2, 256);
     }
     L.bytes = std::max(off, small_net_bytes(d, batch));
     return L;
@@ -817,9 +818,10 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, con
     return ULSNN_OK;
 }
 
-// The same gradient with X, W1, W2 stored as bf16 (operand_dtype 1): H, dO and dA1 are kept in bf16 and fed to
-// the bf16 matrix instructions, every product accumulates in fp32, logits, softmax, loss and the weight gradients
-// stay fp32.
+// The same gradient with X, W1, W2 stored as bf16 (operand_dtype 1): H, the logits and dA1 are kept in bf16 and fed
+// to the bf16 matrix instructions, every product accumulates in fp32; the softmax statistics and the loss come from
+// the fp32 accumulators of the output layer, the output delta exists only in registers (formed from the bf16 logits
+// inside the two products that consume it), and the weight gradients are fp32.
 int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const u16 *X, const MlpTask &task,
                     int batch, float *dW1, float *dW2, float *loss, bool accumulate, hipEvent_t *ev)
 {
@@ -832,8 +834,10 @@ int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const
     char *ws = (char *)d->workspace;
     u16 *H = (u16 *)(ws + L.off_h);
     float2 *stats = (float2 *)(ws + L.off_z);
-    u16 *dO = (u16 *)(ws + L.off_do16);          // the output delta, bf16
-    u16 *Z16 = (u16 *)(ws + L.off_z16);          // softmax form: the logits, bf16
+    // one rows x ldz bf16 array: the logits (softmax form; the delta is formed from them inside the backward
+    // products and never stored) or the output delta (squared-error form, written by the output layer's epilogue)
+    u16 *dO = (u16 *)(ws + L.off_do16);
+    u16 *Z16 = dO;
     float *zlab = (float *)(ws + L.off_zlab);
     float *row_lse = (float *)(ws + L.off_lse);
     u16 *dA1 = (u16 *)(ws + L.off_da1);
@@ -911,17 +915,20 @@ int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const
             continue;
         }
 
-        // dA1 = (dO W2^T) * (1 - H*H), stored bf16.  Softmax form: the product reads the LOGITS and forms
-        // dO = softmax - onehot on the way into LDS, writing it out for the dW2 product and the bias gradient
-        // (no pass of its own over the 2 x batch x n_out bytes of logits and delta)
+        // dA1 = (dO W2^T) * (1 - H*H), stored bf16, and dW2 (+)= H^T dO.  Softmax form: both products read the
+        // LOGITS and form dO = softmax - onehot on the way into LDS; the delta is never stored (no pass over the
+        // 2 x batch x n_out bytes of logits and delta, and no write of the delta, which cost the hidden-delta
+        // product a third of its time).  Squared-error form: the delta came out of the output layer's epilogue.
         Gemm16Args a4{};
         a4.A = ts ? dO : Z16; a4.lda = L.ldz; a4.B = W2; a4.ldb = ldw2; a4.C = dA1; a4.ldc = L.ldh;
         a4.M = rows; a4.N = n_hid; a4.K = n_out; a4.alpha = 1.f; a4.aux = H; a4.ldaux = L.ldh;
-        if (!ts) { a4.row_lse = row_lse; a4.labels = ys; a4.delta_out = dO; }
-        // dW2 (+)= H^T dO
         Gemm16Args a3{};
-        a3.A = H; a3.lda = L.ldh; a3.B = dO; a3.ldb = L.ldz; a3.C = dW2; a3.ldc = n_out;
+        a3.A = H; a3.lda = L.ldh; a3.B = ts ? dO : Z16; a3.ldb = L.ldz; a3.C = dW2; a3.ldc = n_out;
         a3.M = n_hid; a3.N = n_out; a3.K = rows; a3.alpha = 1.f; a3.beta = beta;
+        if (!ts) {
+            a4.row_lse = row_lse; a4.labels = ys;
+            a3.row_lse = row_lse; a3.labels = ys;
+        }
         {
             Gemm16Args q4 = a4, q3 = a3;
             if (p4.splits > 1) { q4.C = part_b; q4.partial_stride = (size_t)a4.M * a4.N; }
@@ -963,8 +970,12 @@ int mlp_grad_impl16(const ulsnn_mlp_desc *d, const u16 *W1, const u16 *W2, const
         MARK(7);
 
         if (biases) {
-            hipLaunchKernelGGL(column_sum16_kernel, dim3((n_out + 63) / 64), dim3(256), 0, s, dO, L.ldz, rows, n_out,
-                               d->db2, beta);
+            if (ts)
+                hipLaunchKernelGGL(column_sum16_kernel, dim3((n_out + 63) / 64), dim3(256), 0, s, dO, L.ldz, rows, n_out,
+                                   d->db2, beta);
+            else
+                hipLaunchKernelGGL(column_sum16_delta_kernel, dim3((n_out + 63) / 64), dim3(256), 0, s, Z16, L.ldz, rows,
+                                   n_out, (const float *)row_lse, ys, d->db2, beta);
             hipLaunchKernelGGL(column_sum16_kernel, dim3((n_hid + 63) / 64), dim3(256), 0, s, dA1, L.ldh, rows, n_hid,
                                d->db1, beta);
             HIP_TRY(hipGetLastError());
