@@ -231,6 +231,17 @@ constexpr int gemm16_lds_elems()
     return 2 * (Panel16<A_KC, Cfg::BM>::SIZE + Panel16<B_KC, Cfg::BN>::SIZE);
 }
 
+// tanh for a result that is rounded to bf16 straight away: tanh|x| = (1 - t) / (1 + t) with t = exp(-2|x|), one
+// exponential and one reciprocal, no case distinction.  Absolute error about 1e-7 (the cancellation in 1 - t), i.e.
+// relative error below the bf16 rounding (2^-9) for |x| > 3e-5 and an absolute error far below any bf16 quantum that
+// matters for smaller ones.  (tanh_f32, which the fp32 results use, keeps full relative accuracy with a series for
+// small arguments, at about twice the instructions.)
+__device__ __forceinline__ float tanh_for_bf16(float x)
+{
+    const float t = __builtin_amdgcn_exp2f(-2.8853900817779268f * fabsf(x));      // 2 log2(e)
+    return copysignf((1.0f - t) * __builtin_amdgcn_rcpf(1.0f + t), x);
+}
+
 // Merge two (max, sum of exp(. - max)) pairs of disjoint column sets; a pair of an empty set is (-inf, 0).
 __device__ __forceinline__ void softmax_merge(float &m, float &s, float om, float os)
 {
@@ -333,21 +344,34 @@ __device__ __forceinline__ void gemm16_epilogue(const Gemm16Args &g, floatx16 (&
                         }
                         rs[pass] += err;
                     } else {
-                    float bm = -INFINITY, zl = 0.f;
+                    // (the whole vector lies inside the matrix except in the last column tile, and the label falls
+                    // into this vector once per row: both cases are kept out of the per-element work)
+                    const bool whole = j + 7 < g.N;
+                    if (g.bias) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const bool in = j + e < g.N;
-                        v[e] += (g.bias && in) ? g.bias[j + e] : 0.f;
-                        bm = in ? fmaxf(bm, v[e]) : bm;
-                        zl = (lab[pass] == j + e) ? v[e] : zl;
+                        for (int e = 0; e < 8; ++e) v[e] += (whole || j + e < g.N) ? g.bias[j + e] : 0.f;
                     }
+                    if (!whole) {
+#pragma unroll
+                        for (int e = 1; e < 8; ++e) v[e] = j + e < g.N ? v[e] : -INFINITY;   // exp(-inf) = 0
+                    }
+                    const float bm = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])),
+                                           fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
                     const float nm = fmaxf(rm[pass], bm);      // finite: column j itself is inside the matrix
+                    const float nml = -nm * 1.44269504088896340736f;       // exp(v - nm) = 2^(v log2e - nm log2e)
                     float bs = 0.f;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) bs += (j + e < g.N) ? __expf(v[e] - nm) : 0.f;
+                    for (int e = 0; e < 8; ++e)
+                        bs += __builtin_amdgcn_exp2f(__builtin_fmaf(v[e], 1.44269504088896340736f, nml));
                     rs[pass] = (rm[pass] == nm ? rs[pass] : rs[pass] * __expf(rm[pass] - nm)) + bs;
                     rm[pass] = nm;
-                    if (lab[pass] >= j && lab[pass] < j + 8 && lab[pass] < g.N) g.label_logit[i] = zl;
+                    const unsigned at_label = (unsigned)(lab[pass] - j);
+                    if (at_label < 8u && lab[pass] < g.N) {
+                        float zl = v[0];
+#pragma unroll
+                        for (int e = 1; e < 8; ++e) zl = at_label == (unsigned)e ? v[e] : zl;
+                        g.label_logit[i] = zl;
+                    }
                     }
                     if (EPI == EPI_BIAS_STATS || EPI == EPI_TANH_MSE) {
                         const u16x8 o = f32x8_to_bf16x8(v);
@@ -429,7 +453,7 @@ __device__ __forceinline__ void gemm16_epilogue(const Gemm16Args &g, floatx16 (&
                     }
                     if (EPI == EPI_BIAS_TANH) {
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) v[e] = tanh_f32(v[e]);
+                        for (int e = 0; e < 8; ++e) v[e] = tanh_for_bf16(v[e]);
                     }
                     if (OUT_BF16) {
                         const u16x8 o = f32x8_to_bf16x8(v);
@@ -483,7 +507,7 @@ __device__ __forceinline__ void gemm16_epilogue(const Gemm16Args &g, floatx16 (&
                 } else if (EPI == EPI_PARTIAL) {
                     Cf[at] = v;
                 } else if (EPI == EPI_BIAS_TANH) {
-                    Ch[at] = f32_to_bf16(tanh_f32(v + bias));
+                    Ch[at] = f32_to_bf16(tanh_for_bf16(v + bias));
                 } else if (EPI == EPI_BIAS) {
                     Cf[at] = v + bias;
                 } else {
