@@ -333,12 +333,17 @@ __device__ __forceinline__ void gemm16_epilogue(const Gemm16Args &g, floatx16 (&
 #pragma unroll
                             for (int e = 0; e < 8; ++e) t[e] = j + e < g.N ? tp[e] : 0.f;
                         }
+                        const bool whole = j + 7 < g.N;
+                        if (g.bias) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[e] += (whole || j + e < g.N) ? g.bias[j + e] : 0.f;
+                        }
                         float err = 0.f;
 #pragma unroll
                         for (int e = 0; e < 8; ++e) {
-                            const bool in = j + e < g.N;
-                            const float yv = tanh_f32(v[e] + ((g.bias && in) ? g.bias[j + e] : 0.f));
-                            const float diff = in ? yv - t[e] : 0.f;
+                            // (the delta is rounded to bf16; the error is summed from y with an absolute error of 1e-7)
+                            const float yv = tanh_for_bf16(v[e]);
+                            const float diff = (whole || j + e < g.N) ? yv - t[e] : 0.f;
                             err += diff * diff;
                             v[e] = 2.0f * diff * (1.0f - yv * yv);
                         }
