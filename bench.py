@@ -527,12 +527,13 @@ def main():
         r["workload"] = "same net, X/W/H/dO/dA1 in bf16, fp32 accumulate, batch 65536"
         # HBM side of this workload: every tensor the step cannot avoid moving, once each way as listed
         n_i, n_h, n_o = shape.n_in, shape.n_hid, shape.n_out
-        alg = 65536 * (n_i + 4 * n_h + 4 * n_o) * 2 + 3 * 2 * (n_i * n_h + n_h * n_o) + 4 * (n_i * n_h + n_h * n_o)
+        alg = 65536 * (n_i + 4 * n_h + 3 * n_o) * 2 + 3 * 2 * (n_i * n_h + n_h * n_o) + 4 * (n_i * n_h + n_h * n_o)
         gbs = alg / (r["ms"] * 1e-3) / 1e9
         r["roofline_hbm"] = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                              "frac": round(gbs / PEAK_HBM_GBS, 4), "algorithmic_bytes": alg,
-                             "algorithmic_bytes_note": "X read; H, logits, delta, dA1 written once and read once (bf16); "
-                                                       "bf16 weights read by three products; fp32 gradients written",
+                             "algorithmic_bytes_note": "X read; H and dA1 written once and read once, logits written once and "
+                                                       "read twice (bf16; the delta is never stored); bf16 weights read by "
+                                                       "three products; fp32 gradients written",
                              "traffic": pmc_traffic(TRAFFIC_PROFILE_BF16).get("bf16_gradient"),
                              "traffic_unit": "bytes of HBM per gradient (calibrated PMC, all kernels)",
                              "traffic_source": TRAFFIC_PROFILE_BF16}

@@ -373,7 +373,7 @@ def test_bench_reads_its_traffic_figures_from_the_committed_profiles():
     # the paired backward launch moves at least its algorithmic bytes (read dO twice, H, W2; write the partials)
     assert fp32["backward_products"] >= 2 * 4096 * 3203 * 4 + 4096 * 480 * 4 + 480 * 3203 * 4
     bf16 = bench.pmc_traffic(bench.TRAFFIC_PROFILE_BF16)
-    assert bf16["bf16_gradient"] >= 65536 * (400 + 4 * 480 + 4 * 3203) * 2
+    assert bf16["bf16_gradient"] >= 65536 * (400 + 4 * 480 + 3 * 3203) * 2
 
 
 def test_sgemm_ws_plan_splits_only_where_it_pays():
