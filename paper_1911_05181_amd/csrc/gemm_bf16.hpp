@@ -111,10 +111,15 @@ struct Panel16 {
 
 __device__ __forceinline__ u16x8 load8_aligned(const u16 *p) { return *reinterpret_cast<const u16x8 *>(p); }
 
-// Checked element-wise fetch of this thread's share of a panel (rows r0.., k from k0, valid k < kend).
-template <bool KC, int R, int THREADS, int NV>
+// Checked fetch of this thread's share of a panel (rows r0.., k from k0, valid k < kend), zero filled.  With VEC and
+// 16-byte aligned rows (`aligned`: pointer and leading dimension multiples of 8 elements) a vector that lies wholly
+// inside the k range is one 16-byte load (an m-contiguous vector that starts inside the matrix stays inside its row,
+// see FastFetch16); everything else goes element by element.  VEC is for the forward products, whose k is a layer
+// width and often no multiple of 32 (n_in = 400: the hidden layer at 65536 patterns 60 -> 54 us); in the long-k
+// backward kernels the extra code cost more than the one partial step it speeds up.
+template <bool KC, int R, int THREADS, int NV, bool VEC>
 __device__ __forceinline__ void panel16_fetch_checked(u16x8 (&reg)[NV], const u16 *__restrict__ P, int ld, int r0,
-                                                      int rmax, int k0, int kend, int tid)
+                                                      int rmax, int k0, int kend, int tid, bool aligned)
 {
     constexpr int TOTAL = R * 32 / 8;
 #pragma unroll
@@ -127,18 +132,26 @@ __device__ __forceinline__ void panel16_fetch_checked(u16x8 (&reg)[NV], const u1
                 const int gr = r0 + row, gk = k0 + kq;
                 if (gr < rmax) {
                     const u16 *src = P + (size_t)gr * ld + gk;
+                    if (VEC && aligned && gk + 7 < kend) {
+                        val = load8_aligned(src);
+                    } else {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (gk + e < kend) val[e] = src[e];
+                        for (int e = 0; e < 8; ++e)
+                            if (gk + e < kend) val[e] = src[e];
+                    }
                 }
             } else {
                 const int krow = f / (R / 8), rq = (f % (R / 8)) * 8;
                 const int gk = k0 + krow, gr = r0 + rq;
                 if (gk < kend) {
                     const u16 *src = P + (size_t)gk * ld + gr;
+                    if (VEC && aligned && gr < rmax) {
+                        val = load8_aligned(src);
+                    } else {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (gr + e < rmax) val[e] = src[e];
+                        for (int e = 0; e < 8; ++e)
+                            if (gr + e < rmax) val[e] = src[e];
+                    }
                 }
             }
         }
@@ -678,8 +691,8 @@ __device__ __forceinline__ void gemm16_tile(const Gemm16Args &g, const int hw, c
         nk += BK;
     };
     auto fetch_checked = [&](const int slot, const int k0) {
-        panel16_fetch_checked<A_KC, BM, THREADS, NVA>(ra[slot], g.A, g.lda, i0, g.M, k0, kend, tid);
-        panel16_fetch_checked<B_KC, BN, THREADS, NVB>(rb[slot], g.B, g.ldb, j0, g.N, k0, kend, tid);
+        panel16_fetch_checked<A_KC, BM, THREADS, NVA, A_KC && !B_KC>(ra[slot], g.A, g.lda, i0, g.M, k0, kend, tid, g.aligned != 0);
+        panel16_fetch_checked<B_KC, BN, THREADS, NVB, A_KC && !B_KC>(rb[slot], g.B, g.ldb, j0, g.N, k0, kend, tid, g.aligned != 0);
         fetch_b_meta(slot, k0, true);
     };
     if (nkb > 0) {
