@@ -18,7 +18,6 @@
 #include <stddef.h>
 #include <stdint.h>
 
-#include <type_traits>
 
 #include "gemm.hpp"
 

@@ -57,13 +57,11 @@ __device__ __forceinline__ float block_sum(float v, float *red)
 //     z_c <- p_c - [c == label]            (the output delta; zero row if the label is out of range)
 //     row_loss[r] = m + ln s - z_label     (0 if the label is out of range)
 // The row is read from HBM once into registers (PER values per thread), so Z is read once and written once.
-// With OUT_BF16 the delta is written, rounded to bf16, to `out16` (row stride ld16) and Z is left untouched.
 // With WRITE_DELTA = false only the row loss is produced (error-only evaluation): Z is read and nothing else written.
-template <int THREADS, int PER, bool OUT_BF16 = false, bool WRITE_DELTA = true>
+template <int THREADS, int PER, bool WRITE_DELTA = true>
 __global__ __launch_bounds__(THREADS) void softmax_ce_kernel(float *__restrict__ Z, int ldz, int n,
                                                              const int32_t *__restrict__ labels,
-                                                             float *__restrict__ row_loss,
-                                                             u16 *__restrict__ out16 = nullptr, int ld16 = 0)
+                                                             float *__restrict__ row_loss)
 {
     __shared__ float red[THREADS / 64];
     const int r = blockIdx.x;
@@ -95,19 +93,16 @@ __global__ __launch_bounds__(THREADS) void softmax_ce_kernel(float *__restrict__
     for (int e = 0; e < PER; ++e) {
         const int c = threadIdx.x + e * THREADS;
         if (c < n) {
-            const float d = labelled ? v[e] * inv - (c == y ? 1.0f : 0.0f) : 0.0f;
-            if (OUT_BF16) out16[(size_t)r * ld16 + c] = f32_to_bf16(d);
-            else z[c] = d;
+            z[c] = labelled ? v[e] * inv - (c == y ? 1.0f : 0.0f) : 0.0f;
         }
     }
 }
 
 // Same operation for rows too long for registers: three passes over the row (the re-reads hit in cache).
-template <int THREADS, bool OUT_BF16 = false, bool WRITE_DELTA = true>
+template <int THREADS, bool WRITE_DELTA = true>
 __global__ __launch_bounds__(THREADS) void softmax_ce_long_kernel(float *__restrict__ Z, int ldz, int n,
                                                                   const int32_t *__restrict__ labels,
-                                                                  float *__restrict__ row_loss,
-                                                                  u16 *__restrict__ out16 = nullptr, int ld16 = 0)
+                                                                  float *__restrict__ row_loss)
 {
     __shared__ float red[THREADS / 64];
     const int r = blockIdx.x;
@@ -125,9 +120,7 @@ __global__ __launch_bounds__(THREADS) void softmax_ce_long_kernel(float *__restr
     if (!WRITE_DELTA) return;
     __syncthreads();
     for (int c = threadIdx.x; c < n; c += THREADS) {
-        const float d = labelled ? __expf(z[c] - m) * inv - (c == y ? 1.0f : 0.0f) : 0.0f;
-        if (OUT_BF16) out16[(size_t)r * ld16 + c] = f32_to_bf16(d);
-        else z[c] = d;
+        z[c] = labelled ? __expf(z[c] - m) * inv - (c == y ? 1.0f : 0.0f) : 0.0f;
     }
 }
 

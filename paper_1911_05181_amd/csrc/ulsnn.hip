@@ -726,17 +726,17 @@ int mlp_grad_impl(const ulsnn_mlp_desc *d, const void *W1v, const void *W2v, con
         } else if (n_out <= 256 * 16) {
             if (task.backward)
                 hipLaunchKernelGGL((softmax_ce_kernel<256, 16>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out, ys,
-                                   row_loss, (u16 *)nullptr, 0);
+                                   row_loss);
             else
-                hipLaunchKernelGGL((softmax_ce_kernel<256, 16, false, false>), dim3(rows), dim3(256), 0, s, Z, L.ldz,
-                                   n_out, ys, row_loss, (u16 *)nullptr, 0);
+                hipLaunchKernelGGL((softmax_ce_kernel<256, 16, false>), dim3(rows), dim3(256), 0, s, Z, L.ldz,
+                                   n_out, ys, row_loss);
         } else {
             if (task.backward)
                 hipLaunchKernelGGL((softmax_ce_long_kernel<256>), dim3(rows), dim3(256), 0, s, Z, L.ldz, n_out, ys,
-                                   row_loss, (u16 *)nullptr, 0);
+                                   row_loss);
             else
-                hipLaunchKernelGGL((softmax_ce_long_kernel<256, false, false>), dim3(rows), dim3(256), 0, s, Z, L.ldz,
-                                   n_out, ys, row_loss, (u16 *)nullptr, 0);
+                hipLaunchKernelGGL((softmax_ce_long_kernel<256, false>), dim3(rows), dim3(256), 0, s, Z, L.ldz,
+                                   n_out, ys, row_loss);
         }
         // Small batches: the dW2 reduction and the loss sum ride along with the dW1 product's launch (whose
         // partials then go to the hidden-delta region, free by then).
